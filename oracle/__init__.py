@@ -1,0 +1,165 @@
+"""ctypes front end of the CPU oracle (``frspec_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by the smoke check and by the
+benchmark's cpu_baseline leg.  The GPU package never imports this module and
+this module never imports the GPU package.
+
+Arrays are numpy: bf16 tensors travel as ``uint16`` bit patterns.
+"""
+
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "frspec_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP, no fast-math).  Returns the .so path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        i64, i32, vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p
+        lib.oracle_build_subset.argtypes = [vp, i64, i64, vp, i64, vp, vp]
+        lib.oracle_logits_f32.argtypes = [vp, i64, i64, vp, i64, vp]
+        lib.oracle_logits_f64.argtypes = [vp, i64, i64, vp, i64, vp]
+        lib.oracle_log_softmax.argtypes = [vp, i64, i64, vp, vp]
+        lib.oracle_topk.argtypes = [vp, i64, i64, vp, i32, vp, vp]
+        lib.oracle_draft_topk.argtypes = [vp, i64, i64, vp, vp, i64, i32, vp, vp, vp]
+        lib.oracle_full_topk.argtypes = [vp, i64, i64, vp, i64, i32, vp, vp, vp]
+        lib.oracle_num_threads.argtypes = []
+        for name in ("oracle_build_subset", "oracle_logits_f32", "oracle_logits_f64",
+                     "oracle_log_softmax", "oracle_topk", "oracle_draft_topk",
+                     "oracle_full_topk", "oracle_num_threads"):
+            getattr(lib, name).restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+class OracleError(RuntimeError):
+    pass
+
+
+def _check(status: int, what: str) -> None:
+    if status != 0:
+        raise OracleError(f"{what} failed with status {status}")
+
+
+def _u16(a, shape_len):
+    a = np.ascontiguousarray(a, dtype=np.uint16)
+    assert a.ndim == shape_len
+    return a
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def build_subset(W_full, freq_ranked_ids, V_sub):
+    """Eq. 3.  Returns (W_sub uint16 [V_sub, d], idx_map int32 [V_sub])."""
+    W_full = _u16(W_full, 2)
+    ids = np.ascontiguousarray(freq_ranked_ids, dtype=np.int32)
+    V, d = W_full.shape
+    if not (1 <= V_sub <= min(V, ids.size)):
+        raise OracleError("V_sub out of range")
+    W_sub = np.empty((V_sub, d), dtype=np.uint16)
+    idx_map = np.empty(V_sub, dtype=np.int32)
+    _check(_load().oracle_build_subset(_p(W_full), V, d, _p(ids), V_sub, _p(W_sub), _p(idx_map)),
+           "oracle_build_subset")
+    return W_sub, idx_map
+
+
+def logits_f32(H, W):
+    """fp32-accumulated logits z [M, rows]."""
+    H, W = _u16(H, 2), _u16(W, 2)
+    M, d = H.shape
+    rows = W.shape[0]
+    assert W.shape[1] == d
+    z = np.empty((M, rows), dtype=np.float32)
+    _check(_load().oracle_logits_f32(_p(H), M, d, _p(W), rows, _p(z)), "oracle_logits_f32")
+    return z
+
+
+def logits_f64(H, W):
+    """fp64-accumulated logits [M, rows] (the exact value up to fp64 rounding)."""
+    H, W = _u16(H, 2), _u16(W, 2)
+    M, d = H.shape
+    rows = W.shape[0]
+    assert W.shape[1] == d
+    z = np.empty((M, rows), dtype=np.float64)
+    _check(_load().oracle_logits_f64(_p(H), M, d, _p(W), rows, _p(z)), "oracle_logits_f64")
+    return z
+
+
+def log_softmax(z):
+    """Returns (logp float32 [M, rows], logZ float64 [M])."""
+    z = np.ascontiguousarray(z, dtype=np.float32)
+    M, rows = z.shape
+    logp = np.empty_like(z)
+    logZ = np.empty(M, dtype=np.float64)
+    _check(_load().oracle_log_softmax(_p(z), M, rows, _p(logp), _p(logZ)), "oracle_log_softmax")
+    return logp, logZ
+
+
+def topk(z, idx_map, k):
+    """Returns (token_ids int32 [M, k], positions int32 [M, k])."""
+    z = np.ascontiguousarray(z, dtype=np.float32)
+    M, rows = z.shape
+    im = None if idx_map is None else np.ascontiguousarray(idx_map, dtype=np.int32)
+    ids = np.empty((M, k), dtype=np.int32)
+    pos = np.empty((M, k), dtype=np.int32)
+    _check(_load().oracle_topk(_p(z), M, rows, _p(im), k, _p(ids), _p(pos)), "oracle_topk")
+    return ids, pos
+
+
+def draft_topk(H, W_sub, idx_map, k, want_logits=False):
+    """Eq. 4, candidate selection, id translation.
+
+    Returns (token_ids int32 [M,k], logp float32 [M,k]) and, if asked, the
+    full fp32 logits [M, V_sub] as a third element.
+    """
+    H, W_sub = _u16(H, 2), _u16(W_sub, 2)
+    M, d = H.shape
+    V_sub = W_sub.shape[0]
+    assert W_sub.shape[1] == d
+    im = None if idx_map is None else np.ascontiguousarray(idx_map, dtype=np.int32)
+    ids = np.empty((M, k), dtype=np.int32)
+    logp = np.empty((M, k), dtype=np.float32)
+    z = np.empty((M, V_sub), dtype=np.float32) if want_logits else None
+    _check(_load().oracle_draft_topk(_p(H), M, d, _p(W_sub), _p(im), V_sub, k,
+                                     _p(ids), _p(logp), _p(z)), "oracle_draft_topk")
+    return (ids, logp, z) if want_logits else (ids, logp)
+
+
+def full_topk(H, W_full, k, want_logits=False):
+    """Eq. 2 with the same candidate selection; position == id."""
+    H, W_full = _u16(H, 2), _u16(W_full, 2)
+    M, d = H.shape
+    V = W_full.shape[0]
+    ids = np.empty((M, k), dtype=np.int32)
+    logp = np.empty((M, k), dtype=np.float32)
+    z = np.empty((M, V), dtype=np.float32) if want_logits else None
+    _check(_load().oracle_full_topk(_p(H), M, d, _p(W_full), V, k, _p(ids), _p(logp), _p(z)),
+           "oracle_full_topk")
+    return (ids, logp, z) if want_logits else (ids, logp)
