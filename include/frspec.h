@@ -1,0 +1,170 @@
+/*
+ * frspec.h - C ABI of the frequency-ranked draft LM head for AMD MI355X (gfx950).
+ *
+ * The operations are those of FR-Spec, Section 3.2:
+ *   Eq. 3  build the sub-matrix W~ whose i-th row is row V_high[i] of W_LM;
+ *   Eq. 4  draft distribution Softmax(H_D W~^T), normalised over the subset;
+ *   Eq. 2  the uncompressed draft distribution Softmax(H_D W_LM^T);
+ * followed by the per-row selection of the k most probable tokens that the
+ * EAGLE-2 beam search of Section 2 consumes, reported as full-vocabulary ids
+ * (Section 3.2: only drafting is restricted, verification keeps the full
+ * vocabulary, so every id that leaves the draft head is a full-vocabulary id).
+ *
+ * Conventions common to every call
+ *   - All data pointers are DEVICE pointers into memory owned by the caller.
+ *     The library allocates nothing, frees nothing and keeps no global state.
+ *   - bf16 tensors are row-major arrays of 16-bit patterns, 16-byte aligned.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ *     default stream) and the call returns without synchronising.  Outputs
+ *     are valid once the stream has been synchronised.
+ *   - Argument errors are detected on the host before anything is launched and
+ *     reported through the return value; nothing is thrown, nothing aborts.
+ *   - Indices are 0-based.
+ */
+#ifndef FRSPEC_H
+#define FRSPEC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int fr_status;
+typedef void *fr_stream;
+
+#define FR_OK 0
+#define FR_ERR_INVALID_ARG (-1) /* null pointer, size < 1, k > rows, k > FR_K_MAX, V_sub > V, d % 8 != 0 */
+#define FR_ERR_ALIGNMENT (-2)   /* a bf16 tensor or the workspace is not 16-byte aligned */
+#define FR_ERR_WORKSPACE (-3)   /* workspace smaller than fr_workspace_bytes() */
+#define FR_ERR_HIP (-4)         /* the HIP runtime refused a launch or a query */
+#define FR_ERR_UNSUPPORTED (-5) /* a shape outside what the kernels cover (see fr_draft_topk) */
+
+#define FR_K_MAX 64 /* largest k accepted by the top-k calls */
+
+/* Human-readable text for a status code; never NULL; static storage. */
+const char *fr_strerror(fr_status status);
+
+/*
+ * Eq. 3:  W_sub[i, :] = W_full[freq_ranked_ids[i], :]  and  idx_map[i] = freq_ranked_ids[i]
+ * for i in [0, V_sub).  A bit copy: W_sub holds exactly the bytes of the chosen rows.
+ *
+ *   W_full           in   bf16 [V, d] row-major
+ *   freq_ranked_ids  in   int32 [>= V_sub], ids ordered by corpus frequency, most frequent
+ *                         first (Section 3.2, "Corpus-Level Token Statistics").  The list
+ *                         is a set: duplicates are the caller's responsibility.
+ *   W_sub            out  bf16 [V_sub, d] row-major (this layout is part of the contract)
+ *   idx_map          out  int32 [V_sub]
+ *   dev_error_flag   out  optional int32 on the device.  The host cannot see the ids
+ *                         without a synchronisation, so range checking is done by the
+ *                         kernel: an id outside [0, V) leaves that row of W_sub
+ *                         untouched, stores -1 in idx_map[i] and sets *dev_error_flag
+ *                         to 1.  The flag is never cleared by the library.
+ * Requires d % 8 == 0 (rows are whole 16-byte chunks), 1 <= V_sub <= V.
+ * W_sub must not overlap W_full.
+ */
+fr_status fr_build_subset(const void *W_full, int64_t V, int64_t d,
+                          const int32_t *freq_ranked_ids, int64_t V_sub,
+                          void *W_sub, int32_t *idx_map, int32_t *dev_error_flag,
+                          fr_stream stream);
+
+/*
+ * Scratch needed by fr_draft_topk / fr_full_topk for a problem of this size (bytes; 0 if
+ * the arguments are invalid).  Pure host arithmetic: usable without a GPU.
+ * The same workspace may serve any call whose requirement is not larger.
+ */
+size_t fr_workspace_bytes(int64_t M, int64_t d, int64_t V_rows, int32_t k);
+
+/*
+ * Prepares a freshly allocated workspace (clears the arrival counter that the fused
+ * kernel uses to find the last workgroup).  Call once per workspace before its first use,
+ * and again if a call using it was ever abandoned mid-flight.  Every completed call
+ * leaves the workspace ready for the next one.  Calls that share a workspace must be
+ * ordered on one stream.
+ */
+fr_status fr_workspace_init(void *workspace, size_t workspace_bytes, fr_stream stream);
+
+/*
+ * Eq. 4, candidate selection and id translation in one pass over W_sub:
+ *   z[m, i]    = sum_j H[m, j] * W_sub[i, j]          bf16 products, fp32 accumulation
+ *   logp[m, i] = z[m, i] - log sum_{i' < V_sub} exp(z[m, i'])   (the subset only)
+ *   for each row m: the k entries with the largest z, most probable first, equal z
+ *   ordered by lower full-vocabulary id; reported as idx_map[i] (i itself if idx_map is
+ *   NULL) together with their logp.
+ * The logits are never written to memory; W_sub is read exactly once.
+ *
+ *   H          in   bf16 [M, d] row-major, one row per draft-tree node
+ *   W_sub      in   bf16 [V_sub, d] row-major (from fr_build_subset)
+ *   idx_map    in   int32 [V_sub] or NULL for the identity
+ *   token_ids  out  int32 [M, k] full-vocabulary ids
+ *   logp       out  fp32  [M, k]
+ *   workspace       >= fr_workspace_bytes(M, d, V_sub, k) bytes, 16-byte aligned,
+ *                   prepared by fr_workspace_init
+ * Requires M >= 1, d % 8 == 0, 1 <= k <= min(V_sub, FR_K_MAX), V_sub < 2^31.
+ * M <= 16 runs on the vector ALUs; larger M runs on the matrix cores in slabs of up to
+ * 256 rows of H.  FR_ERR_UNSUPPORTED is returned if M <= 16 and d is so large that the
+ * M rows of H do not fit the 160 KB of LDS together with the kernel's own state.
+ * NaN or infinite inputs give unspecified outputs but never a fault or a hang.
+ */
+fr_status fr_draft_topk(const void *H, int64_t M, int64_t d,
+                        const void *W_sub, const int32_t *idx_map, int64_t V_sub,
+                        int32_t k, int32_t *token_ids, float *logp,
+                        void *workspace, size_t workspace_bytes, fr_stream stream);
+
+/*
+ * Eq. 2: the same operation over every row of W_full (position == token id).  This is the
+ * uncompressed EAGLE-2 draft head, kept as the baseline the subset is measured against.
+ */
+fr_status fr_full_topk(const void *H, int64_t M, int64_t d,
+                       const void *W_full, int64_t V, int32_t k,
+                       int32_t *token_ids, float *logp,
+                       void *workspace, size_t workspace_bytes, fr_stream stream);
+
+/*
+ * Verification aid (not on the drafting path): runs the same contraction kernels as
+ * fr_draft_topk but stores the logits of Eq. 4 instead of consuming them.
+ *   z_out  out  fp32 [M, V_rows] row-major
+ */
+fr_status fr_draft_logits(const void *H, int64_t M, int64_t d,
+                          const void *W, int64_t V_rows, float *z_out, fr_stream stream);
+
+/*
+ * Kernel-selection knobs for measurements and for tests that force one code path.
+ * A zero in any field means "library default".
+ */
+typedef struct fr_tuning {
+    int32_t path;        /* 1 = vector-ALU skinny kernel, 2 = matrix-core kernel */
+    int32_t two_launch;  /* 1 = merge the per-workgroup partials in a second launch instead
+                            of in the last workgroup to arrive (single launch) */
+    int32_t variant;     /* skinny kernel build variant (pipeline depth / waves), 0..FR_NUM_VARIANTS-1 mapped from 1.. */
+    int32_t ksplit;      /* waves that share one 16-row tile along d (1, 2, 4, 8) */
+    int32_t grid;        /* number of workgroups (<= 512) */
+    int32_t stream_only; /* 1 = measurement only: run the contraction and drop the logits
+                            (no softmax, no top-k; token_ids / logp are left untouched) */
+    int32_t reserved[2];
+} fr_tuning;
+
+/* fr_draft_topk with explicit knobs (tuning == NULL behaves exactly like fr_draft_topk). */
+fr_status fr_draft_topk_tuned(const void *H, int64_t M, int64_t d,
+                              const void *W_sub, const int32_t *idx_map, int64_t V_sub,
+                              int32_t k, int32_t *token_ids, float *logp,
+                              void *workspace, size_t workspace_bytes, fr_stream stream,
+                              const fr_tuning *tuning);
+
+/*
+ * Bandwidth calibration kernels: a plain copy and a plain read of `bytes` bytes
+ * (multiple of 16), used to scale hardware counters and to report what a trivial
+ * streaming kernel achieves on the same machine.  `sink` receives one 16-byte value
+ * (only so that the read cannot be optimised away).
+ */
+fr_status fr_calib_copy(void *dst, const void *src, size_t bytes, fr_stream stream);
+fr_status fr_calib_read(const void *src, size_t bytes, void *sink, fr_stream stream);
+
+/* Library version, major*100 + minor. */
+int fr_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FRSPEC_H */

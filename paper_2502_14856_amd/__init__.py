@@ -1,0 +1,25 @@
+"""MI355X-native frequency-ranked draft LM head (FR-Spec, Section 3.2).
+
+Thin ctypes binding over ``libfrspec.so`` (see ``include/frspec.h``).  Every step
+of the path runs in the HIP kernels; this module only marshals arguments.  There
+is no CPU fallback: importing the binding without the built library raises.
+"""
+
+from .binding import (  # noqa: F401
+    FR_K_MAX,
+    FrSpecError,
+    Tuning,
+    fr_build_subset,
+    fr_calib_copy,
+    fr_calib_read,
+    fr_draft_logits,
+    fr_draft_topk,
+    fr_full_topk,
+    fr_strerror,
+    fr_version,
+    fr_workspace_bytes,
+    fr_workspace_init,
+    lib,
+    lib_path,
+    new_workspace,
+)

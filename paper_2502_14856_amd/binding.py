@@ -1,0 +1,213 @@
+"""ctypes marshalling for libfrspec.so.  Names and argument order follow include/frspec.h.
+
+Tensors are torch CUDA (ROCm) tensors: bf16 data may be passed as ``torch.bfloat16``
+or as its bit patterns (``torch.int16`` / ``torch.uint16``).  Work is enqueued on
+torch's current stream unless ``stream`` (a raw hipStream_t integer) is given.
+"""
+
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libfrspec.so")
+
+FR_K_MAX = 64
+
+
+class FrSpecError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {fr_strerror(status)} (status {status})")
+
+
+class Tuning(ctypes.Structure):
+    """Mirror of ``fr_tuning``; zero fields mean library default."""
+    _fields_ = [("path", ctypes.c_int32), ("two_launch", ctypes.c_int32),
+                ("variant", ctypes.c_int32), ("ksplit", ctypes.c_int32),
+                ("grid", ctypes.c_int32), ("stream_only", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 2)]
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib():
+    """The loaded library.  Fails loudly if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2502_14856_amd.build` "
+                "(there is no fallback implementation)")
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
+        L.fr_strerror.argtypes = [ctypes.c_int]
+        L.fr_strerror.restype = ctypes.c_char_p
+        L.fr_version.argtypes = []
+        L.fr_version.restype = ctypes.c_int
+        L.fr_build_subset.argtypes = [vp, i64, i64, vp, i64, vp, vp, vp, vp]
+        L.fr_workspace_bytes.argtypes = [i64, i64, i64, i32]
+        L.fr_workspace_bytes.restype = sz
+        L.fr_workspace_init.argtypes = [vp, sz, vp]
+        L.fr_draft_topk.argtypes = [vp, i64, i64, vp, vp, i64, i32, vp, vp, vp, sz, vp]
+        L.fr_draft_topk_tuned.argtypes = [vp, i64, i64, vp, vp, i64, i32, vp, vp, vp, sz, vp,
+                                          ctypes.POINTER(Tuning)]
+        L.fr_full_topk.argtypes = [vp, i64, i64, vp, i64, i32, vp, vp, vp, sz, vp]
+        L.fr_draft_logits.argtypes = [vp, i64, i64, vp, i64, vp, vp]
+        L.fr_calib_copy.argtypes = [vp, vp, sz, vp]
+        L.fr_calib_read.argtypes = [vp, sz, vp, vp]
+        for name in ("fr_build_subset", "fr_workspace_init", "fr_draft_topk", "fr_draft_topk_tuned",
+                     "fr_full_topk", "fr_draft_logits", "fr_calib_copy", "fr_calib_read"):
+            getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def fr_strerror(status: int) -> str:
+    return lib().fr_strerror(int(status)).decode()
+
+
+def fr_version() -> int:
+    return int(lib().fr_version())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    return ctypes.c_void_p(int(stream))
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _is_bf16_like(t):
+    return t.dtype in (torch.bfloat16, torch.int16, torch.uint16)
+
+
+def _check(status, what):
+    if status != 0:
+        raise FrSpecError(status, what)
+
+
+def _bf16_matrix(t, name):
+    if not (t.is_cuda and t.dim() == 2 and t.is_contiguous() and _is_bf16_like(t)):
+        raise ValueError(f"{name} must be a contiguous 2-D CUDA tensor of bf16 (or its 16-bit patterns)")
+    return t
+
+
+def fr_workspace_bytes(M: int, d: int, V_rows: int, k: int) -> int:
+    return int(lib().fr_workspace_bytes(M, d, V_rows, k))
+
+
+def fr_workspace_init(workspace, stream=None) -> None:
+    _check(lib().fr_workspace_init(_ptr(workspace), workspace.numel() * workspace.element_size(),
+                                   _stream(stream)), "fr_workspace_init")
+
+
+def new_workspace(M: int, d: int, V_rows: int, k: int, device="cuda", stream=None):
+    """Allocates (torch) and prepares a workspace large enough for the given problem."""
+    n = fr_workspace_bytes(M, d, V_rows, k)
+    if n == 0:
+        raise ValueError("invalid problem size for a workspace")
+    ws = torch.empty(n, dtype=torch.uint8, device=device)
+    fr_workspace_init(ws, stream)
+    return ws
+
+
+def fr_build_subset(W_full, freq_ranked_ids, V_sub: int, W_sub=None, idx_map=None,
+                    dev_error_flag=None, stream=None):
+    """Eq. 3.  Returns (W_sub, idx_map); outputs are allocated if not supplied."""
+    _bf16_matrix(W_full, "W_full")
+    V, d = W_full.shape
+    if not (freq_ranked_ids.is_cuda and freq_ranked_ids.dtype == torch.int32
+            and freq_ranked_ids.is_contiguous() and freq_ranked_ids.numel() >= V_sub):
+        raise ValueError("freq_ranked_ids must be a contiguous CUDA int32 tensor with >= V_sub entries")
+    if W_sub is None:
+        W_sub = torch.empty((V_sub, d), dtype=W_full.dtype, device=W_full.device)
+    if idx_map is None:
+        idx_map = torch.empty(V_sub, dtype=torch.int32, device=W_full.device)
+    _check(lib().fr_build_subset(_ptr(W_full), V, d, _ptr(freq_ranked_ids), V_sub, _ptr(W_sub),
+                                 _ptr(idx_map), _ptr(dev_error_flag), _stream(stream)),
+           "fr_build_subset")
+    return W_sub, idx_map
+
+
+def _head_outputs(M, k, device, token_ids, logp):
+    if token_ids is None:
+        token_ids = torch.empty((M, k), dtype=torch.int32, device=device)
+    if logp is None:
+        logp = torch.empty((M, k), dtype=torch.float32, device=device)
+    return token_ids, logp
+
+
+def fr_draft_topk(H, W_sub, idx_map, k: int, workspace, token_ids=None, logp=None, stream=None,
+                  tuning: Tuning | None = None):
+    """Eq. 4 + per-row top-k + id remap.  Returns (token_ids int32 [M,k], logp fp32 [M,k])."""
+    _bf16_matrix(H, "H")
+    _bf16_matrix(W_sub, "W_sub")
+    M, d = H.shape
+    V_sub = W_sub.shape[0]
+    if W_sub.shape[1] != d:
+        raise ValueError("H and W_sub disagree on d")
+    if idx_map is not None and not (idx_map.is_cuda and idx_map.dtype == torch.int32
+                                    and idx_map.is_contiguous() and idx_map.numel() >= V_sub):
+        raise ValueError("idx_map must be a contiguous CUDA int32 tensor with >= V_sub entries")
+    token_ids, logp = _head_outputs(M, k, H.device, token_ids, logp)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    if tuning is None:
+        st = lib().fr_draft_topk(_ptr(H), M, d, _ptr(W_sub), _ptr(idx_map), V_sub, k,
+                                 _ptr(token_ids), _ptr(logp), _ptr(workspace), ws_bytes,
+                                 _stream(stream))
+    else:
+        st = lib().fr_draft_topk_tuned(_ptr(H), M, d, _ptr(W_sub), _ptr(idx_map), V_sub, k,
+                                       _ptr(token_ids), _ptr(logp), _ptr(workspace), ws_bytes,
+                                       _stream(stream), ctypes.byref(tuning))
+    _check(st, "fr_draft_topk")
+    return token_ids, logp
+
+
+def fr_full_topk(H, W_full, k: int, workspace, token_ids=None, logp=None, stream=None):
+    """Eq. 2 with the same candidate selection.  Returns (token_ids, logp)."""
+    _bf16_matrix(H, "H")
+    _bf16_matrix(W_full, "W_full")
+    M, d = H.shape
+    V = W_full.shape[0]
+    if W_full.shape[1] != d:
+        raise ValueError("H and W_full disagree on d")
+    token_ids, logp = _head_outputs(M, k, H.device, token_ids, logp)
+    _check(lib().fr_full_topk(_ptr(H), M, d, _ptr(W_full), V, k, _ptr(token_ids), _ptr(logp),
+                              _ptr(workspace), workspace.numel() * workspace.element_size(),
+                              _stream(stream)), "fr_full_topk")
+    return token_ids, logp
+
+
+def fr_draft_logits(H, W, z_out=None, stream=None):
+    """Verification aid: the logits of Eq. 4 as fp32 [M, V_rows]."""
+    _bf16_matrix(H, "H")
+    _bf16_matrix(W, "W")
+    M, d = H.shape
+    V_rows = W.shape[0]
+    if z_out is None:
+        z_out = torch.empty((M, V_rows), dtype=torch.float32, device=H.device)
+    _check(lib().fr_draft_logits(_ptr(H), M, d, _ptr(W), V_rows, _ptr(z_out), _stream(stream)),
+           "fr_draft_logits")
+    return z_out
+
+
+def fr_calib_copy(dst, src, stream=None) -> None:
+    nbytes = src.numel() * src.element_size()
+    _check(lib().fr_calib_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "fr_calib_copy")
+
+
+def fr_calib_read(src, sink, stream=None) -> None:
+    nbytes = src.numel() * src.element_size()
+    _check(lib().fr_calib_read(_ptr(src), nbytes, _ptr(sink), _stream(stream)), "fr_calib_read")

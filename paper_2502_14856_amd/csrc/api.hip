@@ -1,0 +1,219 @@
+// C ABI of libfrspec: argument validation on the host, workspace carving, dispatch.
+#include <mutex>
+
+#include "internal.hpp"
+
+namespace frspec {
+
+int device_cu_count() {
+    static std::mutex mu;
+    static int cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return -1;
+    std::lock_guard<std::mutex> lock(mu);
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            return -1;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
+namespace {
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
+
+struct WorkspaceLayout {
+    size_t ms_off, val_off, id_off, total;
+    WorkspaceLayout(int64_t M, int32_t k) {
+        const size_t rows = static_cast<size_t>(M < kMatrixPathMaxM ? M : kMatrixPathMaxM);
+        const size_t slots = static_cast<size_t>(kWorkspaceGridMax) * rows;
+        size_t o = kWorkspaceHeaderBytes;
+        ms_off = o;  o += round256(slots * 2 * sizeof(float));
+        val_off = o; o += round256(slots * static_cast<size_t>(k) * sizeof(float));
+        id_off = o;  o += round256(slots * static_cast<size_t>(k) * sizeof(int));
+        total = o;
+    }
+};
+
+fr_status check_head_args(const void *H, int64_t M, int64_t d, const void *W, int64_t V_rows,
+                          int32_t k) {
+    if (!H || !W) return FR_ERR_INVALID_ARG;
+    if (M < 1 || d < 8 || (d % 8) != 0 || V_rows < 1 || V_rows > INT32_MAX) return FR_ERR_INVALID_ARG;
+    if (M > INT32_MAX || d > (1 << 24)) return FR_ERR_INVALID_ARG;
+    if (k < 1 || k > FR_K_MAX || k > V_rows) return FR_ERR_INVALID_ARG;
+    if (V_rows * (d / 8) > INT32_MAX) return FR_ERR_INVALID_ARG;   // 16-byte chunk index fits int32
+    if (!aligned16(H) || !aligned16(W)) return FR_ERR_ALIGNMENT;
+    return FR_OK;
+}
+
+fr_status head_topk(const void *H, int64_t M, int64_t d, const void *W, const int32_t *idx_map,
+                    int64_t V_rows, int32_t k, int32_t *token_ids, float *logp, void *workspace,
+                    size_t workspace_bytes, fr_stream stream, const fr_tuning *tuning) {
+    fr_status st = check_head_args(H, M, d, W, V_rows, k);
+    if (st != FR_OK) return st;
+    if (!token_ids || !logp || !workspace) return FR_ERR_INVALID_ARG;
+    if (!aligned16(workspace)) return FR_ERR_ALIGNMENT;
+    const WorkspaceLayout wl(M, k);
+    if (workspace_bytes < wl.total) return FR_ERR_WORKSPACE;
+    if (tuning && (tuning->path < 0 || tuning->path > 2 || tuning->grid < 0 ||
+                   tuning->grid > kWorkspaceGridMax || tuning->variant < 0 || tuning->ksplit < 0))
+        return FR_ERR_INVALID_ARG;
+
+    char *ws = static_cast<char *>(workspace);
+    HeadProblem p{};
+    p.W = W;
+    p.idx_map = idx_map;
+    p.d = static_cast<int>(d);
+    p.V_rows = static_cast<int>(V_rows);
+    p.k = k;
+    p.ws.ticket = reinterpret_cast<unsigned *>(ws);
+    p.ws.part_ms = reinterpret_cast<float *>(ws + wl.ms_off);
+    p.ws.part_val = reinterpret_cast<float *>(ws + wl.val_off);
+    p.ws.part_id = reinterpret_cast<int *>(ws + wl.id_off);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    int path = tuning ? tuning->path : 0;
+    if (path == 0) path = (M <= kSkinnyMaxM && skinny_fits((int)M, (int)d, k)) ? 1 : 2;
+    const bool two_launch = tuning && tuning->two_launch;
+    const bool stream_only = tuning && tuning->stream_only;
+
+    if (path == 1) {
+        if (M > kSkinnyMaxM) return FR_ERR_UNSUPPORTED;
+        p.H = H;
+        p.M = static_cast<int>(M);
+        p.token_ids = token_ids;
+        p.logp = logp;
+        return launch_skinny(p, stream_only ? Sink::kStreamOnly : two_launch ? Sink::kPartialsOnly : Sink::kFusedTopk, tuning, s);
+    }
+
+    // matrix-core path: slabs of H rows, each a full pass over W
+    const int slab = mfma_max_rows(k);
+    if (slab <= 0) return FR_ERR_UNSUPPORTED;
+    for (int64_t m0 = 0; m0 < M; m0 += slab) {
+        const int rows = static_cast<int>(M - m0 < slab ? M - m0 : slab);
+        p.H = static_cast<const char *>(H) + static_cast<size_t>(m0) * d * 2;
+        p.M = rows;
+        p.token_ids = token_ids + m0 * k;
+        p.logp = logp + m0 * k;
+        // one workgroup merging every row only pays off while the rows are few
+        const Sink sink = stream_only ? Sink::kStreamOnly
+                          : (two_launch || rows > 32) ? Sink::kPartialsOnly : Sink::kFusedTopk;
+        st = launch_mfma(p, sink, tuning, s, nullptr);
+        if (st != FR_OK) return st;
+    }
+    return FR_OK;
+}
+
+}  // namespace
+}  // namespace frspec
+
+using namespace frspec;
+
+extern "C" {
+
+const char *fr_strerror(fr_status status) {
+    switch (status) {
+        case FR_OK: return "ok";
+        case FR_ERR_INVALID_ARG: return "invalid argument";
+        case FR_ERR_ALIGNMENT: return "pointer not 16-byte aligned";
+        case FR_ERR_WORKSPACE: return "workspace too small";
+        case FR_ERR_HIP: return "HIP runtime error";
+        case FR_ERR_UNSUPPORTED: return "shape not supported by the kernels";
+    }
+    return "unknown status";
+}
+
+int fr_version(void) { return 100; }
+
+fr_status fr_build_subset(const void *W_full, int64_t V, int64_t d, const int32_t *freq_ranked_ids,
+                          int64_t V_sub, void *W_sub, int32_t *idx_map, int32_t *dev_error_flag,
+                          fr_stream stream) {
+    if (!W_full || !freq_ranked_ids || !W_sub || !idx_map) return FR_ERR_INVALID_ARG;
+    if (V < 1 || V > INT32_MAX || d < 8 || (d % 8) != 0 || d > (1 << 24)) return FR_ERR_INVALID_ARG;
+    if (V_sub < 1 || V_sub > V) return FR_ERR_INVALID_ARG;
+    if (!aligned16(W_full) || !aligned16(W_sub)) return FR_ERR_ALIGNMENT;
+    return launch_gather(W_full, V, d, freq_ranked_ids, V_sub, W_sub, idx_map, dev_error_flag,
+                         static_cast<hipStream_t>(stream));
+}
+
+size_t fr_workspace_bytes(int64_t M, int64_t d, int64_t V_rows, int32_t k) {
+    if (M < 1 || d < 8 || (d % 8) != 0 || V_rows < 1 || k < 1 || k > FR_K_MAX || k > V_rows) return 0;
+    return WorkspaceLayout(M, k).total;
+}
+
+fr_status fr_workspace_init(void *workspace, size_t workspace_bytes, fr_stream stream) {
+    if (!workspace) return FR_ERR_INVALID_ARG;
+    if (!aligned16(workspace)) return FR_ERR_ALIGNMENT;
+    if (workspace_bytes < kWorkspaceHeaderBytes) return FR_ERR_WORKSPACE;
+    return launch_fill_u32(static_cast<unsigned *>(workspace), kWorkspaceHeaderBytes / 4, 0u,
+                           static_cast<hipStream_t>(stream));
+}
+
+fr_status fr_draft_topk(const void *H, int64_t M, int64_t d, const void *W_sub,
+                        const int32_t *idx_map, int64_t V_sub, int32_t k, int32_t *token_ids,
+                        float *logp, void *workspace, size_t workspace_bytes, fr_stream stream) {
+    return head_topk(H, M, d, W_sub, idx_map, V_sub, k, token_ids, logp, workspace, workspace_bytes,
+                     stream, nullptr);
+}
+
+fr_status fr_draft_topk_tuned(const void *H, int64_t M, int64_t d, const void *W_sub,
+                              const int32_t *idx_map, int64_t V_sub, int32_t k, int32_t *token_ids,
+                              float *logp, void *workspace, size_t workspace_bytes,
+                              fr_stream stream, const fr_tuning *tuning) {
+    return head_topk(H, M, d, W_sub, idx_map, V_sub, k, token_ids, logp, workspace, workspace_bytes,
+                     stream, tuning);
+}
+
+fr_status fr_full_topk(const void *H, int64_t M, int64_t d, const void *W_full, int64_t V, int32_t k,
+                       int32_t *token_ids, float *logp, void *workspace, size_t workspace_bytes,
+                       fr_stream stream) {
+    return head_topk(H, M, d, W_full, nullptr, V, k, token_ids, logp, workspace, workspace_bytes,
+                     stream, nullptr);
+}
+
+fr_status fr_draft_logits(const void *H, int64_t M, int64_t d, const void *W, int64_t V_rows,
+                          float *z_out, fr_stream stream) {
+    fr_status st = check_head_args(H, M, d, W, V_rows, 1);
+    if (st != FR_OK) return st;
+    if (!z_out) return FR_ERR_INVALID_ARG;
+    HeadProblem p{};
+    p.W = W;
+    p.d = static_cast<int>(d);
+    p.V_rows = static_cast<int>(V_rows);
+    p.k = 1;
+    p.z_ld = static_cast<int>(V_rows);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (M <= kSkinnyMaxM && skinny_fits((int)M, (int)d, 1)) {
+        p.H = H;
+        p.M = static_cast<int>(M);
+        p.z_out = z_out;
+        return launch_skinny(p, Sink::kLogits, nullptr, s);
+    }
+    const int slab = mfma_max_rows(1);
+    for (int64_t m0 = 0; m0 < M; m0 += slab) {
+        const int rows = static_cast<int>(M - m0 < slab ? M - m0 : slab);
+        p.H = static_cast<const char *>(H) + static_cast<size_t>(m0) * d * 2;
+        p.M = rows;
+        p.z_out = z_out + static_cast<size_t>(m0) * V_rows;
+        st = launch_mfma(p, Sink::kLogits, nullptr, s, nullptr);
+        if (st != FR_OK) return st;
+    }
+    return FR_OK;
+}
+
+fr_status fr_calib_copy(void *dst, const void *src, size_t bytes, fr_stream stream) {
+    if (!dst || !src || (bytes % 16) != 0) return FR_ERR_INVALID_ARG;
+    if (!aligned16(dst) || !aligned16(src)) return FR_ERR_ALIGNMENT;
+    return launch_copy(dst, src, bytes, static_cast<hipStream_t>(stream));
+}
+
+fr_status fr_calib_read(const void *src, size_t bytes, void *sink, fr_stream stream) {
+    if (!src || !sink || (bytes % 16) != 0) return FR_ERR_INVALID_ARG;
+    if (!aligned16(src) || !aligned16(sink)) return FR_ERR_ALIGNMENT;
+    return launch_read(src, bytes, sink, static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,74 @@
+// Host-side declarations shared by the translation units of libfrspec.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/frspec.h"
+
+namespace frspec {
+
+// What a contraction kernel does with the logits of a tile.
+enum class Sink : int {
+    kFusedTopk = 0,    // fold into partials; the last workgroup to arrive merges them
+    kPartialsOnly = 1, // fold into partials; a merge kernel follows
+    kLogits = 2,       // store the logits (verification aid)
+    kStreamOnly = 3,   // drop the logits (measures the contraction alone)
+};
+
+// Device-side view of the workspace.
+struct WorkspaceView {
+    unsigned *ticket;
+    float *part_ms;
+    float *part_val;
+    int *part_id;
+};
+
+struct HeadProblem {
+    const void *H;        // bf16 [M, d]
+    const void *W;        // bf16 [V_rows, d]
+    const int *idx_map;   // nullable
+    int M, d, V_rows, k;
+    int *token_ids;       // [M, k]
+    float *logp;          // [M, k]
+    float *z_out;         // [M, V_rows] (Sink::kLogits only)
+    int z_ld;             // leading dimension of z_out
+    WorkspaceView ws;
+};
+
+constexpr size_t kWorkspaceHeaderBytes = 256;
+constexpr int kWorkspaceGridMax = 512;   // partial slots reserved per row of H
+constexpr int kMatrixPathMaxM = 256;     // rows of H per matrix-core launch
+constexpr int kSkinnyMaxM = 16;          // rows of H the vector-ALU kernel covers
+
+// Number of compute units of the current device (cached per device); <= 0 on error.
+int device_cu_count();
+
+// skinny.hip: vector-ALU kernel for M <= 16.  Returns FR_ERR_UNSUPPORTED if H does not fit LDS.
+fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hipStream_t s);
+// Largest LDS the skinny kernel would need, for workspace-free feasibility checks.
+bool skinny_fits(int M, int d, int k);
+
+// mfma.hip: matrix-core kernel for 1 <= M <= 256.
+fr_status launch_mfma(const HeadProblem &p, Sink sink, const fr_tuning *t, hipStream_t s,
+                      int *grid_used);
+// Largest slab of H rows (multiple of 16, <= 256) whose per-row state fits LDS for this k.
+int mfma_max_rows(int k);
+
+// merge.hip: merges G partial slots per row of H into the outputs.
+fr_status launch_merge(const HeadProblem &p, int G, hipStream_t s);
+
+// gather.hip
+fr_status launch_gather(const void *W_full, int64_t V, int64_t d, const int32_t *ids,
+                        int64_t V_sub, void *W_sub, int32_t *idx_map, int32_t *flag,
+                        hipStream_t s);
+
+// calib.hip
+fr_status launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
+fr_status launch_read(const void *src, size_t bytes, void *sink, hipStream_t s);
+fr_status launch_fill_u32(unsigned *dst, size_t n, unsigned value, hipStream_t s);
+
+inline fr_status hip_status(hipError_t e) { return e == hipSuccess ? FR_OK : FR_ERR_HIP; }
+
+}  // namespace frspec

@@ -1,0 +1,441 @@
+// Vector-ALU kernel for a handful of H rows (M <= 16): the streaming skinny product of
+// Eq. 4 fused with the online log-softmax, the per-row top-k and the id remap.
+//
+// The product is bound by reading W once from HBM (2*d bytes per vocabulary row against
+// 2*M*d flops), so the kernel is organised around the stream of W:
+//   * one persistent workgroup per compute unit keeps all M rows of H in LDS;
+//   * a wavefront owns a tile of 16 vocabulary rows.  Its 64 lanes form 4 row slots of
+//     16 lanes; a slot walks along d, each lane loading 16 bytes (8 bf16) of W per step,
+//     so one load instruction fetches 256 contiguous bytes from each of 4 rows.  Every
+//     lane serves 4 rows, which lets one 16-byte LDS read of H feed 4 rows of W;
+//   * W goes straight from HBM to registers through a software pipeline of DEPTH steps;
+//     products use the packed bf16 dot instruction with fp32 accumulation;
+//   * after the last step the 16 lanes of a slot are summed with DPP rotations; the
+//     tile's logits go to LDS, never to HBM.
+// For small vocabularies several wavefronts share a tile and split d between them
+// (KS > 1) so that every compute unit still has enough loads in flight.
+#include "epilogue.hpp"
+#include "internal.hpp"
+
+namespace frspec {
+namespace {
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float dot2_bf16(unsigned w, unsigned h, float acc) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w),
+                                           __builtin_bit_cast(bf16x2_t, h), acc, false);
+}
+
+// Streaming load of 16 bytes of W: global address space, wave-uniform base, per-lane
+// unsigned 32-bit byte offset, non-temporal (W is read once and must not evict H).
+typedef const __attribute__((address_space(1))) char *GlobalBytes;
+typedef const __attribute__((address_space(1))) u32x4 *GlobalVec;
+__device__ __forceinline__ u32x4 load_w(GlobalBytes base, unsigned byte_offset) {
+    return __builtin_nontemporal_load(reinterpret_cast<GlobalVec>(base + byte_offset));
+}
+
+constexpr int kTileRows = 16;     // vocabulary rows per wavefront tile
+constexpr int kRowsPerLane = 4;   // rows served by one lane
+constexpr int kLanesAlongD = 16;  // lanes of a row slot (one DPP row)
+
+struct SkinnyArgs {
+    const u32x4 *H;
+    const u32x4 *W;
+    const int *idx_map;
+    int M, d8, V_rows, k;
+    int KS;               // wavefronts sharing one tile along d
+    int steps;            // ceil(d8 / 16): steps of 128 elements along d
+    int steps_per_split;  // ceil(steps / KS)
+    int passes;           // ceil(V_rows / rows per pass)
+    int sink;
+    Partials part;
+    unsigned *ticket;
+    int *token_ids;
+    float *logp;
+    float *z_out;
+    int z_ld;
+};
+
+__host__ __device__ constexpr int round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+// LDS carve-up, in bytes, identical on host and device.
+struct SkinnyLds {
+    int h_off, z_off, ids_off, ms_off, val_off, id_off, total;
+    __host__ __device__ SkinnyLds(int MT, int waves, int steps, int k) {
+        int o = 0;
+        h_off = o;   o += MT * steps * kLanesAlongD * 16;
+        z_off = o;   o += (waves * kTileRows * MT + waves * kTileRows) * 4;
+        ids_off = o; o += waves * kTileRows * 4;
+        ms_off = o;  o += MT * 2 * 4;
+        val_off = o; o += MT * k * 4;
+        id_off = o;  o += MT * k * 4;
+        total = round_up(o, 16);
+    }
+};
+
+template <int MT, int WAVES, int DEPTH>
+__global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
+    extern __shared__ u32x4 smem[];
+    char *base = reinterpret_cast<char *>(smem);
+    const SkinnyLds L(MT, WAVES, a.steps, a.k);
+    u32x4 *H_lds = reinterpret_cast<u32x4 *>(base + L.h_off);
+    float *z_lds = reinterpret_cast<float *>(base + L.z_off);
+    int *ids_lds = reinterpret_cast<int *>(base + L.ids_off);
+    float *run_ms = reinterpret_cast<float *>(base + L.ms_off);
+    float *run_val = reinterpret_cast<float *>(base + L.val_off);
+    int *run_id = reinterpret_cast<int *>(base + L.id_off);
+    __shared__ int s_is_last;
+
+    constexpr int ZR_MAX = WAVES * kTileRows;
+    constexpr int kStep16 = kLanesAlongD;        // 16-byte chunks per row per step
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // wave-uniform by construction
+    const int lk = lane & (kLanesAlongD - 1);
+    const int rs = lane / kLanesAlongD;
+    const int hpitch = a.steps * kStep16;        // 16-byte chunks per padded row of H
+    const int KS = a.KS;
+    const int ZR = (WAVES / KS) * kTileRows;     // vocabulary rows per pass
+    const int tile_in_pass = wave / KS;
+    const int ks = wave - tile_in_pass * KS;
+    const int G = gridDim.x;
+
+    // Step range of this wavefront along d, split into a pipelined part (whole groups of
+    // DEPTH full steps, no bounds handling at all) and leftovers (at most DEPTH - 1 steps,
+    // plus the ragged last step when d is not a multiple of 128).
+    const int s_begin = ks * a.steps_per_split;
+    const int s_end = min(a.steps, s_begin + a.steps_per_split);
+    const int full_end = min(s_end, a.d8 / kStep16);
+    const int groups = full_end > s_begin ? (full_end - s_begin) / DEPTH : 0;
+    const int s_pipe_end = s_begin + groups * DEPTH;
+    // Every wavefront walks its groups of steps cyclically from a different starting group.
+    // All wavefronts advance at about the same pace; if they also started at the same
+    // column, the whole device would at any moment read addresses that agree modulo the
+    // row pitch and load the memory channels unevenly.  The sum over d does not depend
+    // on the order of the steps.
+    const int g_first = groups > 0 ? (int)((wave + blockIdx.x) % (unsigned)groups) : 0;
+
+    // W is addressed as a wave-uniform base plus a per-lane 32-bit byte offset (the host
+    // guarantees the matrix is smaller than 4 GiB): offset of (row, chunk lk of step
+    // s_begin) for the 4 rows of this lane.
+    const GlobalBytes Wb = (GlobalBytes)a.W;
+    auto row_offsets = [&](int pass, unsigned (&wo)[kRowsPerLane]) {
+        const int tile_row0 = pass * ZR + tile_in_pass * kTileRows + rs * kRowsPerLane;
+#pragma unroll
+        for (int r = 0; r < kRowsPerLane; ++r) {
+            const int row = min(tile_row0 + r, a.V_rows - 1);
+            wo[r] = ((unsigned)row * (unsigned)a.d8 + (unsigned)(s_begin * kStep16 + lk)) * 16u;
+        }
+    };
+    constexpr unsigned kStepBytes = kStep16 * 16;
+    constexpr unsigned kGroupBytes = DEPTH * kStepBytes;
+
+    // W is requested before anything else so that HBM is busy while H is staged
+    u32x4 wb[DEPTH][kRowsPerLane];
+    unsigned wo[kRowsPerLane];
+    int p = blockIdx.x;
+    if (p < a.passes && groups > 0) {
+        row_offsets(p, wo);
+#pragma unroll
+        for (int u = 0; u < DEPTH; ++u)
+#pragma unroll
+            for (int r = 0; r < kRowsPerLane; ++r)
+                wb[u][r] = load_w(Wb, wo[r] + g_first * kGroupBytes + u * kStepBytes);
+    }
+
+    // stage H (zero padded to MT rows and to whole steps) and reset the running state
+    for (int i = tid; i < MT * hpitch; i += WAVES * kWave) {
+        const int m = i / hpitch, c = i - m * hpitch;
+        u32x4 v = zero_u32x4();
+        if (m < a.M && c < a.d8) v = a.H[(size_t)m * a.d8 + c];
+        H_lds[i] = v;
+    }
+    for (int i = tid; i < MT * a.k; i += WAVES * kWave) {
+        run_val[i] = kNegInf;
+        run_id[i] = INT_MAX;
+    }
+    if (tid < MT) {
+        run_ms[2 * tid] = kNegInf;
+        run_ms[2 * tid + 1] = 0.0f;
+    }
+    __syncthreads();
+
+    for (; p < a.passes; p += G) {
+        const int pass_row0 = p * ZR;
+        const int n_valid = min(ZR, a.V_rows - pass_row0);
+        if (tid < n_valid) {
+            const int row = pass_row0 + tid;
+            ids_lds[tid] = a.idx_map ? a.idx_map[row] : row;
+        }
+
+        float acc[kRowsPerLane][MT];
+#pragma unroll
+        for (int r = 0; r < kRowsPerLane; ++r)
+#pragma unroll
+            for (int m = 0; m < MT; ++m) acc[r][m] = 0.0f;
+
+        // one step: 16 bytes of each of the lane's 4 rows against the M rows of H
+        auto compute = [&](const u32x4 (&w)[kRowsPerLane], const u32x4 *hp) {
+            u32x4 h[MT];
+#pragma unroll
+            for (int m = 0; m < MT; ++m) h[m] = hp[m * hpitch];
+#pragma unroll
+            for (int r = 0; r < kRowsPerLane; ++r)
+#pragma unroll
+                for (int m = 0; m < MT; ++m) {
+                    float t = acc[r][m];
+                    t = dot2_bf16(w[r].x, h[m].x, t);
+                    t = dot2_bf16(w[r].y, h[m].y, t);
+                    t = dot2_bf16(w[r].z, h[m].z, t);
+                    t = dot2_bf16(w[r].w, h[m].w, t);
+                    acc[r][m] = t;
+                }
+        };
+
+        if (groups > 0) {
+            const u32x4 *hp0 = H_lds + s_begin * kStep16 + lk;
+            int grp = g_first;
+            // Steady state: consume stage u, then refill it with the same stage of the next
+            // group.  The scheduling barriers keep the refill where it is written: left
+            // alone, the scheduler sinks all loads to the end of the body (shorter live
+            // ranges) and the wavefront then waits for every load it has just issued.
+            for (int it = 0; it < groups - 1; ++it) {
+                const int nxt = (grp + 1 == groups) ? 0 : grp + 1;
+                const u32x4 *hp = hp0 + grp * (DEPTH * kStep16);
+                const unsigned nofs = (unsigned)nxt * kGroupBytes;
+#pragma unroll
+                for (int u = 0; u < DEPTH; ++u) {
+                    compute(wb[u], hp + u * kStep16);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int r = 0; r < kRowsPerLane; ++r)
+                        wb[u][r] = load_w(Wb, wo[r] + nofs + u * kStepBytes);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                grp = nxt;
+            }
+            // drain; the stages freed here start on the next pass of this workgroup
+            const u32x4 *hp = hp0 + grp * (DEPTH * kStep16);
+            const bool has_next = p + G < a.passes;
+            if (has_next) {
+                row_offsets(p + G, wo);
+                const unsigned nofs = (unsigned)g_first * kGroupBytes;
+#pragma unroll
+                for (int u = 0; u < DEPTH; ++u) {
+                    compute(wb[u], hp + u * kStep16);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int r = 0; r < kRowsPerLane; ++r)
+                        wb[u][r] = load_w(Wb, wo[r] + nofs + u * kStepBytes);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < DEPTH; ++u) compute(wb[u], hp + u * kStep16);
+            }
+        }
+        if (s_pipe_end < s_end) {
+            // Leftover steps, not pipelined.  A chunk index past the end of the row is
+            // clamped: the bytes loaded are valid finite weights and the matching H chunk
+            // in LDS is zero.
+            unsigned wr[kRowsPerLane];
+            row_offsets(p, wr);
+            for (int s = s_pipe_end; s < s_end; ++s) {
+                const int c = min(s * kStep16 + lk, a.d8 - 1) - (s_begin * kStep16 + lk);
+                u32x4 w[kRowsPerLane];
+#pragma unroll
+                for (int r = 0; r < kRowsPerLane; ++r) w[r] = load_w(Wb, wr[r] + (unsigned)c * 16u);
+                compute(w, H_lds + s * kStep16 + lk);
+            }
+        }
+
+        // sum the 16 lanes of each row slot; lane 0 of the slot stores the tile's logits
+#pragma unroll
+        for (int r = 0; r < kRowsPerLane; ++r)
+#pragma unroll
+            for (int m = 0; m < MT; ++m) acc[r][m] = row16_sum(acc[r][m]);
+        if (lk == 0) {
+            const int rl = tile_in_pass * kTileRows + rs * kRowsPerLane;
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+#pragma unroll
+                for (int r = 0; r < kRowsPerLane; ++r)
+                    z_lds[(ks * MT + m) * ZR + rl + r] = acc[r][m];
+        }
+        __syncthreads();
+
+        // ---- consume the pass ----
+        if (a.sink == (int)Sink::kLogits) {
+            for (int i = tid; i < a.M * ZR; i += WAVES * kWave) {
+                const int m = i / ZR, r = i - m * ZR;
+                if (r < n_valid) {
+                    float z = 0.0f;
+                    for (int s = 0; s < KS; ++s) z += z_lds[(s * MT + m) * ZR + r];
+                    a.z_out[(size_t)m * a.z_ld + pass_row0 + r] = z;
+                }
+            }
+        } else if (a.sink != (int)Sink::kStreamOnly) {
+            auto row_of = [&](int m) {
+                return FoldRow{z_lds + m * ZR, run_ms + 2 * m, run_val + m * a.k, run_id + m * a.k};
+            };
+            if (p == (int)blockIdx.x)
+                block_fold_all<ZR_MAX, false>(wave, WAVES, a.M, row_of, KS, MT * ZR, ids_lds, n_valid, a.k);
+            else
+                block_fold_all<ZR_MAX, true>(wave, WAVES, a.M, row_of, KS, MT * ZR, ids_lds, n_valid, a.k);
+        }
+        __syncthreads();
+    }
+
+    if (a.sink == (int)Sink::kLogits || a.sink == (int)Sink::kStreamOnly) return;
+
+    // ---- publish this workgroup's partials ----
+    const int g = blockIdx.x;
+    for (int m = wave; m < a.M; m += WAVES) {
+        if (lane < a.k) {
+            publish(a.part.val + part_index(m * a.k + lane, g), run_val[m * a.k + lane]);
+            publish(a.part.id + part_index(m * a.k + lane, g), run_id[m * a.k + lane]);
+        }
+        if (lane < 2) publish(a.part.ms + part_index(m * 2 + lane, g), run_ms[2 * m + lane]);
+    }
+    if (a.sink == (int)Sink::kPartialsOnly) return;
+
+    // ---- the last workgroup to arrive merges all partials (single launch) ----
+    if (!arrive_is_last(a.ticket, G, &s_is_last)) return;
+    final_merge_all(a.part, G, wave, WAVES, a.M, a.k, a.token_ids, a.logp);
+    if (tid == 0) reset_ticket(a.ticket);   // leave the workspace ready for the next call
+}
+
+// ---------------------------------------------------------------- host side ---
+
+constexpr int kLdsBudget = 160 * 1024;   // bytes of LDS per workgroup on gfx950
+
+constexpr int kMTBuckets[] = {1, 2, 4, 6, 8, 10, 12, 16};
+
+int bucket_for(int M) {
+    for (int b : kMTBuckets)
+        if (M <= b) return b;
+    return -1;
+}
+
+template <int MT, int WAVES, int DEPTH>
+fr_status launch_one(const SkinnyArgs &a, int grid, int lds, hipStream_t s) {
+    auto kern = skinny_kernel<MT, WAVES, DEPTH>;
+    static bool attr_done = false;   // raising the dynamic LDS limit is idempotent
+    if (!attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                kLdsBudget - 64) != hipSuccess) {
+            (void)hipGetLastError();
+            return FR_ERR_HIP;
+        }
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(WAVES * kWave), lds, s, a);
+    return hip_status(hipGetLastError());
+}
+
+template <int WAVES, int DEPTH>
+fr_status launch_mt(int MT, const SkinnyArgs &a, int grid, int lds, hipStream_t s) {
+    switch (MT) {
+        case 1: return launch_one<1, WAVES, DEPTH>(a, grid, lds, s);
+        case 2: return launch_one<2, WAVES, DEPTH>(a, grid, lds, s);
+        case 4: return launch_one<4, WAVES, DEPTH>(a, grid, lds, s);
+        case 6: return launch_one<6, WAVES, DEPTH>(a, grid, lds, s);
+        case 8: return launch_one<8, WAVES, DEPTH>(a, grid, lds, s);
+        case 10: return launch_one<10, WAVES, DEPTH>(a, grid, lds, s);
+        case 12: return launch_one<12, WAVES, DEPTH>(a, grid, lds, s);
+        case 16: return launch_one<16, WAVES, DEPTH>(a, grid, lds, s);
+    }
+    return FR_ERR_UNSUPPORTED;
+}
+
+struct Variant {
+    int waves, depth;
+};
+// Build variants (waves per workgroup, pipeline depth).  Variant 0 is what the library
+// uses; the others exist to measure the design space.  With 16 rows of H the accumulators
+// leave room for only two stages of W in the 256 registers of a lane.
+constexpr Variant kVariants[] = {{8, 4}, {8, 2}, {8, 3}, {8, 6}, {16, 2}};
+constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
+
+int default_variant(int MT) { return MT > 10 ? 1 : 0; }
+
+}  // namespace
+
+bool skinny_fits(int M, int d, int k) {
+    const int MT = bucket_for(M);
+    if (MT < 0) return false;
+    const int steps = (d / 8 + kLanesAlongD - 1) / kLanesAlongD;
+    return SkinnyLds(MT, 16, steps, k).total <= kLdsBudget - 1024;
+}
+
+fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hipStream_t s) {
+    const int MT = bucket_for(p.M);
+    if (MT < 0 || !skinny_fits(p.M, p.d, p.k)) return FR_ERR_UNSUPPORTED;
+    int variant = default_variant(MT);
+    if (t && t->variant > 0) {
+        if (t->variant > kNumVariants) return FR_ERR_INVALID_ARG;
+        variant = t->variant - 1;
+    }
+    const int waves = kVariants[variant].waves;
+    const int cus = device_cu_count();
+    if (cus <= 0) return FR_ERR_HIP;
+
+    SkinnyArgs a{};
+    a.H = static_cast<const u32x4 *>(p.H);
+    a.W = static_cast<const u32x4 *>(p.W);
+    a.idx_map = p.idx_map;
+    a.M = p.M;
+    a.d8 = p.d / 8;
+    a.V_rows = p.V_rows;
+    a.k = p.k;
+    a.steps = (a.d8 + kLanesAlongD - 1) / kLanesAlongD;
+
+    // Split d between wavefronts until every compute unit has a workgroup, as far as
+    // the number of steps allows.
+    int KS = 1;
+    if (t && t->ksplit > 0) {
+        KS = t->ksplit;
+        if (KS > waves || (KS & (KS - 1)) != 0) return FR_ERR_INVALID_ARG;
+    } else {
+        auto passes_for = [&](int ks) {
+            const int zr = (waves / ks) * kTileRows;
+            return (p.V_rows + zr - 1) / zr;
+        };
+        while (KS < waves && KS * 2 <= a.steps && passes_for(KS) < cus) KS *= 2;
+    }
+    a.KS = KS;
+    a.steps_per_split = (a.steps + KS - 1) / KS;
+    const int ZR = (waves / KS) * kTileRows;
+    a.passes = (p.V_rows + ZR - 1) / ZR;
+    a.sink = (int)sink;
+    a.part.ms = p.ws.part_ms;
+    a.part.val = p.ws.part_val;
+    a.part.id = p.ws.part_id;
+    a.ticket = p.ws.ticket;
+    a.token_ids = p.token_ids;
+    a.logp = p.logp;
+    a.z_out = p.z_out;
+    a.z_ld = p.z_ld;
+
+    int grid = a.passes < cus ? a.passes : cus;
+    if (t && t->grid > 0) grid = t->grid < a.passes ? t->grid : a.passes;
+    if (grid > kGridMax) grid = kGridMax;
+    const int lds = SkinnyLds(MT, waves, a.steps, p.k).total;
+
+    fr_status st;
+    switch (variant) {
+        case 0: st = launch_mt<8, 4>(MT, a, grid, lds, s); break;
+        case 1: st = launch_mt<8, 2>(MT, a, grid, lds, s); break;
+        case 2: st = launch_mt<8, 3>(MT, a, grid, lds, s); break;
+        case 3: st = launch_mt<8, 6>(MT, a, grid, lds, s); break;
+        case 4: st = launch_mt<16, 2>(MT, a, grid, lds, s); break;
+        default: return FR_ERR_INVALID_ARG;
+    }
+    if (st != FR_OK) return st;
+    if (sink == Sink::kPartialsOnly) return launch_merge(p, grid, s);
+    return FR_OK;
+}
+
+}  // namespace frspec

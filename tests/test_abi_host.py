@@ -1,0 +1,120 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+the header declares, sizes workspaces, and rejects bad arguments before launching anything."""
+
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2502_14856_amd as fr
+from paper_2502_14856_amd.binding import Tuning
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "frspec.h")
+
+INVALID, ALIGN, WORKSPACE = -1, -2, -3
+
+
+def _declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fr_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = fr.lib()
+    names = _declared_symbols()
+    assert {"fr_build_subset", "fr_draft_topk", "fr_full_topk", "fr_workspace_bytes",
+            "fr_workspace_init", "fr_strerror"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_strerror_and_version():
+    assert fr.fr_version() >= 100
+    assert fr.fr_strerror(0) == "ok"
+    for code in (-1, -2, -3, -4, -5, -99):
+        assert fr.fr_strerror(code)
+
+
+def test_workspace_bytes_is_pure_host_arithmetic():
+    a = fr.fr_workspace_bytes(10, 4096, 32768, 10)
+    assert a > 0 and a % 256 == 0
+    assert fr.fr_workspace_bytes(10, 4096, 128256, 10) == a     # independent of the rows read
+    assert fr.fr_workspace_bytes(16, 4096, 32768, 10) > a
+    assert fr.fr_workspace_bytes(10, 4096, 32768, 64) > a
+    assert fr.fr_workspace_bytes(1000, 4096, 32768, 10) == fr.fr_workspace_bytes(256, 4096, 32768, 10)
+    for bad in ((0, 4096, 100, 1), (1, 4095, 100, 1), (1, 4096, 0, 1), (1, 4096, 100, 0),
+                (1, 4096, 100, 65), (1, 4096, 5, 6)):
+        assert fr.fr_workspace_bytes(*bad) == 0
+
+
+def _draft(H=0x1000, M=10, d=4096, W=0x2000, idx=0, V=32768, k=10, ids=0x3000, lp=0x4000,
+           ws=0x5000, ws_bytes=1 << 24):
+    return fr.lib().fr_draft_topk(H, M, d, W, idx, V, k, ids, lp, ws, ws_bytes, None)
+
+
+def test_draft_topk_rejects_bad_arguments_before_any_launch():
+    # the pointers are fake: reaching a kernel launch would be an error in itself
+    assert _draft(H=0) == INVALID
+    assert _draft(W=0) == INVALID
+    assert _draft(ids=0) == INVALID
+    assert _draft(lp=0) == INVALID
+    assert _draft(ws=0) == INVALID
+    assert _draft(M=0) == INVALID
+    assert _draft(d=4100) == INVALID
+    assert _draft(k=0) == INVALID
+    assert _draft(k=65) == INVALID
+    assert _draft(V=5, k=6) == INVALID
+    assert _draft(H=0x1008) == ALIGN
+    assert _draft(W=0x2004) == ALIGN
+    assert _draft(ws=0x5008) == ALIGN
+    assert _draft(ws_bytes=1024) == WORKSPACE
+    need = fr.fr_workspace_bytes(10, 4096, 32768, 10)
+    assert _draft(ws_bytes=need - 1) == WORKSPACE
+
+
+def test_full_topk_and_logits_reject_bad_arguments():
+    L = fr.lib()
+    assert L.fr_full_topk(0, 1, 64, 0x2000, 100, 1, 0x3000, 0x4000, 0x5000, 1 << 24, None) == INVALID
+    assert L.fr_full_topk(0x1000, 1, 64, 0x2000, 100, 101, 0x3000, 0x4000, 0x5000, 1 << 24, None) == INVALID
+    assert L.fr_draft_logits(0x1000, 1, 64, 0x2000, 100, 0, None) == INVALID
+    assert L.fr_draft_logits(0x1001, 1, 64, 0x2000, 100, 0x3000, None) == ALIGN
+
+
+def test_tuned_entry_validates_knobs():
+    t = Tuning()
+    t.path = 7
+    st = fr.lib().fr_draft_topk_tuned(0x1000, 10, 4096, 0x2000, 0, 32768, 10, 0x3000, 0x4000,
+                                      0x5000, 1 << 24, None, ctypes.byref(t))
+    assert st == INVALID
+
+
+def test_build_subset_rejects_bad_arguments():
+    L = fr.lib()
+    ok = dict(W=0x1000, V=100, d=64, ids=0x2000, Vs=10, Ws=0x3000, im=0x4000)
+
+    def call(**kw):
+        a = {**ok, **kw}
+        return L.fr_build_subset(a["W"], a["V"], a["d"], a["ids"], a["Vs"], a["Ws"], a["im"], None, None)
+
+    assert call(W=0) == INVALID and call(ids=0) == INVALID and call(Ws=0) == INVALID and call(im=0) == INVALID
+    assert call(Vs=0) == INVALID and call(Vs=101) == INVALID and call(d=60) == INVALID and call(V=0) == INVALID
+    assert call(W=0x1004) == ALIGN and call(Ws=0x3008) == ALIGN
+
+
+def test_workspace_init_and_calib_reject_bad_arguments():
+    L = fr.lib()
+    assert L.fr_workspace_init(0, 4096, None) == INVALID
+    assert L.fr_workspace_init(0x1000, 16, None) == WORKSPACE
+    assert L.fr_calib_copy(0x1000, 0x2000, 24, None) == INVALID
+    assert L.fr_calib_read(0, 1024, 0x1000, None) == INVALID
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    H = torch.zeros((2, 64), dtype=torch.bfloat16)
+    W = torch.zeros((8, 64), dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        fr.fr_draft_topk(H, W, None, 2, torch.zeros(1 << 20, dtype=torch.uint8))

@@ -1,0 +1,265 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the
+same seeded inputs.  Bar: gather / remap bit-exact; logits within 1e-2 max-abs; top-k ids
+identical except at near ties of the oracle's own logits (< 1e-2); exact-arithmetic
+inputs must agree with no exemption."""
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2502_14856_amd as fr
+from paper_2502_14856_amd.binding import Tuning
+from parity_utils import (LOGIT_TOL, bits_of, check_topk_against_oracle, to_dev_bf16, to_dev_i32)
+from synth import (CONFIGS, bf16_bits_to_f32, f32_to_bf16_bits, make_exact_case, make_hidden, make_weights,
+                   zipf_ranking)
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def _case(V, d, M, seed, w_std=0.05):
+    g = np.random.default_rng([77, seed])
+    W = f32_to_bf16_bits((g.standard_normal((V, d)) * w_std).astype(np.float32))
+    H = f32_to_bf16_bits(g.standard_normal((M, d)).astype(np.float32))
+    r = g.permutation(V).astype(np.int32)
+    return W, H, r
+
+
+def _sync():
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ Eq. 3 ---
+
+@pytest.mark.parametrize("V,d,V_sub", [(8192, 256, 2048), (1000, 264, 1000), (777, 8, 1), (5000, 4096, 1234)])
+def test_build_subset_bit_exact(V, d, V_sub):
+    _say("gather", V, d, V_sub)
+    W, _, r = _case(V, d, 1, 1)
+    W_o, idx_o = oracle.build_subset(W, r, V_sub)
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    W_g, idx_g = fr.fr_build_subset(to_dev_bf16(W), to_dev_i32(r), V_sub, dev_error_flag=flag)
+    _sync()
+    assert np.array_equal(bits_of(W_g), W_o)
+    assert np.array_equal(idx_g.cpu().numpy(), idx_o)
+    assert int(flag.item()) == 0
+
+
+def test_build_subset_flags_bad_ids_without_faulting():
+    _say("gather bad ids")
+    W, _, r = _case(300, 64, 1, 2)
+    bad = r.copy()
+    bad[5] = 300
+    bad[9] = -7
+    W_sub = torch.zeros((20, 64), dtype=torch.bfloat16, device="cuda")
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    W_g, idx_g = fr.fr_build_subset(to_dev_bf16(W), to_dev_i32(bad), 20, W_sub=W_sub, dev_error_flag=flag)
+    _sync()
+    assert int(flag.item()) == 1
+    got, idx = bits_of(W_g), idx_g.cpu().numpy()
+    for i in range(20):
+        if i in (5, 9):
+            assert idx[i] == -1 and not got[i].any()      # row left untouched (zeros)
+        else:
+            assert idx[i] == bad[i] and np.array_equal(got[i], W[bad[i]])
+
+
+def test_tiny_config_generated_ranking_gather():
+    c = CONFIGS["tiny"]
+    _say("gather tiny config")
+    W = make_weights(c.V, c.d, c.index)
+    r, _ = zipf_ranking(c.V, c.zipf_s, c.n_tokens, c.index)
+    W_o, idx_o = oracle.build_subset(W, r, c.V_sub)
+    W_g, idx_g = fr.fr_build_subset(to_dev_bf16(W), to_dev_i32(r), c.V_sub)
+    _sync()
+    assert np.array_equal(bits_of(W_g), W_o) and np.array_equal(idx_g.cpu().numpy(), idx_o)
+
+
+# ----------------------------------------------------------------- logits ---
+
+@pytest.mark.parametrize("M,d,V", [(1, 256, 2048), (4, 256, 2048), (10, 4096, 600), (16, 512, 1000),
+                                   (7, 264, 333), (3, 8, 17), (10, 136, 129), (13, 1024, 4099)])
+def test_logits_skinny_within_tolerance(M, d, V):
+    _say("logits skinny", M, d, V)
+    W, H, _ = _case(V, d, M, 3)
+    z_o = oracle.logits_f32(H, W)
+    z_g = fr.fr_draft_logits(to_dev_bf16(H), to_dev_bf16(W))
+    _sync()
+    err = np.max(np.abs(z_g.cpu().numpy() - z_o))
+    _say("  max abs err", err)
+    assert err <= LOGIT_TOL
+    assert err < 1e-4      # what fp32 accumulation actually delivers at these sizes
+
+
+@pytest.mark.parametrize("M,d,V", [(17, 256, 2048), (60, 512, 1000), (64, 4096, 300), (100, 264, 333),
+                                   (256, 256, 513), (300, 128, 260)])
+def test_logits_matrix_core_within_tolerance(M, d, V):
+    _say("logits mfma", M, d, V)
+    W, H, _ = _case(V, d, M, 4)
+    z_o = oracle.logits_f32(H, W)
+    z_g = fr.fr_draft_logits(to_dev_bf16(H), to_dev_bf16(W))
+    _sync()
+    err = np.max(np.abs(z_g.cpu().numpy() - z_o))
+    _say("  max abs err", err)
+    assert err <= LOGIT_TOL
+    assert err < 1e-4
+
+
+@pytest.mark.parametrize("M", [1, 10, 16, 40, 256])
+def test_logits_exact_inputs_bit_exact(M):
+    _say("logits exact", M)
+    W_bits, H_bits, W_int, H_int = make_exact_case(V=700, d=520, M=M, seed=M)
+    exact = (H_int @ W_int.T).astype(np.float32)
+    z_g = fr.fr_draft_logits(to_dev_bf16(H_bits), to_dev_bf16(W_bits))
+    _sync()
+    assert np.array_equal(z_g.cpu().numpy(), exact)
+
+
+# ------------------------------------------------------------------ top-k ---
+
+def _run_draft(W, H, r, V_sub, k, tuning=None, exact=False):
+    W_o, idx_o = oracle.build_subset(W, r, V_sub)
+    ids_o, lp_o, z_o = oracle.draft_topk(H, W_o, idx_o, k, want_logits=True)
+    M, d = H.shape
+    W_g, idx_g = fr.fr_build_subset(to_dev_bf16(W), to_dev_i32(r), V_sub)
+    ws = fr.new_workspace(M, d, V_sub, k)
+    ids_g, lp_g = fr.fr_draft_topk(to_dev_bf16(H), W_g, idx_g, k, ws, tuning=tuning)
+    _sync()
+    frac = check_topk_against_oracle(ids_g.cpu().numpy(), lp_g.cpu().numpy(), z_o, idx_o, ids_o, lp_o,
+                                     exact=exact)
+    # the workspace must be ready for the next call without re-initialisation
+    ids_g2, lp_g2 = fr.fr_draft_topk(to_dev_bf16(H), W_g, idx_g, k, ws, tuning=tuning)
+    _sync()
+    assert torch.equal(ids_g, ids_g2) and torch.equal(lp_g, lp_g2)
+    return frac, ids_g.cpu().numpy(), lp_g.cpu().numpy()
+
+
+def test_tiny_config_draft_topk():
+    c = CONFIGS["tiny"]
+    _say("draft tiny config")
+    W = make_weights(c.V, c.d, c.index)
+    H = make_hidden(c.M, c.d, c.index)
+    r, _ = zipf_ranking(c.V, c.zipf_s, c.n_tokens, c.index)
+    frac, _, _ = _run_draft(W, H, r, c.V_sub, c.k)
+    _say("  rows identical to the oracle:", frac)
+
+
+@pytest.mark.parametrize("M,d,V,V_sub,k", [
+    (1, 256, 4096, 1024, 1), (10, 512, 6000, 3000, 10), (16, 256, 5000, 2500, 16),
+    (5, 264, 3000, 777, 7), (10, 1024, 9000, 4099, 33), (3, 128, 2000, 1999, 64),
+    (2, 64, 100, 10, 10), (10, 4096, 2000, 640, 10)])
+def test_draft_topk_skinny(M, d, V, V_sub, k):
+    _say("draft skinny", M, d, V, V_sub, k)
+    W, H, r = _case(V, d, M, 5)
+    frac, _, _ = _run_draft(W, H, r, V_sub, k)
+    _say("  rows identical to the oracle:", frac)
+
+
+@pytest.mark.parametrize("M,d,V,V_sub,k", [
+    (17, 256, 4096, 1024, 4), (60, 512, 6000, 3000, 10), (64, 256, 5000, 2500, 16),
+    (100, 264, 3000, 777, 7), (256, 128, 3000, 1500, 10), (300, 64, 2000, 900, 5),
+    (40, 128, 2000, 1999, 64)])
+def test_draft_topk_matrix_core(M, d, V, V_sub, k):
+    _say("draft mfma", M, d, V, V_sub, k)
+    W, H, r = _case(V, d, M, 6)
+    frac, _, _ = _run_draft(W, H, r, V_sub, k)
+    _say("  rows identical to the oracle:", frac)
+
+
+@pytest.mark.parametrize("M", [4, 10, 48])
+def test_draft_topk_exact_inputs_identical_with_ties(M):
+    # Integer-valued inputs: logits are exact on both sides and full of ties, so the
+    # ids must match the oracle with no exemption (this pins the tie rule on the GPU).
+    _say("draft exact + ties", M)
+    W_bits, H_bits, _, _ = make_exact_case(V=3000, d=72, M=M, seed=100 + M, w_levels=1, h_levels=1)
+    r = np.random.default_rng(11).permutation(3000).astype(np.int32)
+    frac, _, _ = _run_draft(W_bits, H_bits, r, 1500, 12, exact=True)
+    assert frac == 1.0
+
+
+def test_duplicate_rows_tie_goes_to_lower_full_vocab_id():
+    _say("draft duplicate rows")
+    W, H, r = _case(4000, 256, 10, 8)
+    # make the best token of every row of H a duplicate pair (higher id ranked first)
+    W[3999] = W[17]
+    H = f32_to_bf16_bits(np.tile(bf16_bits_to_f32(W[17]) * 8, (10, 1)))
+    r = np.concatenate([[3999, 17], np.setdiff1d(np.arange(4000), [17, 3999])]).astype(np.int32)
+    _, ids_g, lp_g = _run_draft(W, H, r, 2000, 4)
+    assert np.all(ids_g[:, 0] == 17) and np.all(ids_g[:, 1] == 3999)
+    assert np.array_equal(lp_g[:, 0], lp_g[:, 1])
+
+
+@pytest.mark.parametrize("knobs", [dict(two_launch=1), dict(ksplit=2), dict(ksplit=8), dict(grid=3),
+                                   dict(grid=1), dict(variant=2), dict(variant=3), dict(variant=4),
+                                   dict(variant=5), dict(path=2), dict(path=2, two_launch=1)])
+def test_kernel_variants_agree(knobs):
+    _say("variants", knobs)
+    W, H, r = _case(6000, 512, 10, 9)
+    base = _run_draft(W, H, r, 3000, 10)
+    t = Tuning()
+    for key, val in knobs.items():
+        setattr(t, key, val)
+    other = _run_draft(W, H, r, 3000, 10, tuning=t)
+    # different summation orders may flip genuine near ties, nothing else
+    same = base[1] == other[1]
+    assert np.mean(same) > 0.9
+    assert np.max(np.abs(base[2] - other[2])) < LOGIT_TOL
+
+
+@pytest.mark.parametrize("M,k", [(10, 10), (64, 10)])
+def test_full_topk_matches_oracle(M, k):
+    _say("full topk", M, k)
+    W, H, _ = _case(5003, 512, M, 10)
+    ids_o, lp_o, z_o = oracle.full_topk(H, W, k, want_logits=True)
+    ws = fr.new_workspace(M, 512, 5003, k)
+    ids_g, lp_g = fr.fr_full_topk(to_dev_bf16(H), to_dev_bf16(W), k, ws)
+    _sync()
+    check_topk_against_oracle(ids_g.cpu().numpy(), lp_g.cpu().numpy(), z_o, None, ids_o, lp_o)
+
+
+def test_v_sub_equal_v_draft_equals_full():
+    _say("V_sub == V")
+    W, H, _ = _case(2048, 256, 10, 12)
+    ident = np.arange(2048, dtype=np.int32)
+    W_g, idx_g = fr.fr_build_subset(to_dev_bf16(W), to_dev_i32(ident), 2048)
+    ws = fr.new_workspace(10, 256, 2048, 10)
+    a = fr.fr_draft_topk(to_dev_bf16(H), W_g, idx_g, 10, ws)
+    b = fr.fr_full_topk(to_dev_bf16(H), to_dev_bf16(W), 10, ws)
+    _sync()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+def test_nan_and_inf_inputs_do_not_hang():
+    _say("nan / inf inputs")
+    W, H, r = _case(2000, 128, 4, 13)
+    W[5, 3] = 0x7FC0    # NaN
+    W[9, 1] = 0x7F80    # +inf
+    H[1, 0] = 0xFF80    # -inf
+    W_g, idx_g = fr.fr_build_subset(to_dev_bf16(W), to_dev_i32(r), 1000)
+    ws = fr.new_workspace(4, 128, 1000, 5)
+    ids_g, lp_g = fr.fr_draft_topk(to_dev_bf16(H), W_g, idx_g, 5, ws)
+    _sync()
+    assert ids_g.shape == (4, 5)
+
+
+def test_workspace_reuse_with_changing_inputs_sees_no_stale_partials():
+    # The single-launch merge reads partials written by workgroups on other compute dies.
+    # Reusing one workspace for different inputs, back to back, would expose a merge that
+    # reads the previous call's partials.
+    _say("workspace reuse, changing inputs")
+    W, _, r = _case(8000, 512, 10, 14)
+    V_sub, k = 4096, 10
+    W_o, idx_o = oracle.build_subset(W, r, V_sub)
+    W_g, idx_g = fr.fr_build_subset(to_dev_bf16(W), to_dev_i32(r), V_sub)
+    ws = fr.new_workspace(10, 512, V_sub, k)
+    g = np.random.default_rng(15)
+    Hs = [f32_to_bf16_bits(g.standard_normal((10, 512)).astype(np.float32)) for _ in range(8)]
+    Hd = [to_dev_bf16(h) for h in Hs]
+    outs = [fr.fr_draft_topk(h, W_g, idx_g, k, ws) for h in Hd]   # enqueued back to back
+    _sync()
+    for h, (ids_g, lp_g) in zip(Hs, outs):
+        ids_o, lp_o, z_o = oracle.draft_topk(h, W_o, idx_o, k, want_logits=True)
+        check_topk_against_oracle(ids_g.cpu().numpy(), lp_g.cpu().numpy(), z_o, idx_o, ids_o, lp_o)
