@@ -19,6 +19,8 @@ oracle and the GPU path see identical bytes.
 
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass
 
 import numpy as np
@@ -87,24 +89,36 @@ def _rng(config_index: int, stream: int, block: int = 0) -> np.random.Generator:
     return np.random.default_rng([BASE_SEED, int(config_index), int(stream), int(block)])
 
 
+def _weights_block(V, d, config_index, std, b0, lo, hi, out):
+    b1 = min(b0 + _W_BLOCK_ROWS, V)
+    g = _rng(config_index, _STREAM_W, b0 // _W_BLOCK_ROWS)
+    blk = g.standard_normal((b1 - b0, d), dtype=np.float32)
+    blk *= np.float32(std)
+    take = min(b1, hi) - b0
+    out[b0 - lo:b0 - lo + take] = f32_to_bf16_bits(blk[:take])
+
+
 def make_weights(V: int, d: int, config_index: int, std: float = 0.02,
-                 rows: slice | None = None) -> np.ndarray:
+                 rows: slice | None = None, threads: int | None = None) -> np.ndarray:
     """bf16 bit patterns of W_full [V, d], row-major, entries ~ N(0, std^2).
 
-    ``rows`` restricts generation to a row range whose start is a multiple of
-    the internal block size (used to stream a large W to the device).
+    Each block of 4096 rows has its own generator stream, so the bytes depend neither on
+    ``rows`` (a row range starting on a block boundary, used to build a large W piecewise)
+    nor on ``threads`` (blocks are filled concurrently).
     """
     lo, hi = (0, V) if rows is None else (rows.start or 0, V if rows.stop is None else rows.stop)
     if lo % _W_BLOCK_ROWS:
         raise ValueError("row range must start on a generator block boundary")
     out = np.empty((hi - lo, d), dtype=np.uint16)
-    for b0 in range(lo, hi, _W_BLOCK_ROWS):
-        b1 = min(b0 + _W_BLOCK_ROWS, V)
-        g = _rng(config_index, _STREAM_W, b0 // _W_BLOCK_ROWS)
-        blk = g.standard_normal((b1 - b0, d), dtype=np.float32)
-        blk *= np.float32(std)
-        take = min(b1, hi) - b0
-        out[b0 - lo:b0 - lo + take] = f32_to_bf16_bits(blk[:take])
+    starts = list(range(lo, hi, _W_BLOCK_ROWS))
+    if threads is None:
+        threads = min(8, os.cpu_count() or 1)
+    if threads <= 1 or len(starts) <= 1:
+        for b0 in starts:
+            _weights_block(V, d, config_index, std, b0, lo, hi, out)
+    else:
+        with ThreadPoolExecutor(max_workers=threads) as ex:
+            list(ex.map(lambda b0: _weights_block(V, d, config_index, std, b0, lo, hi, out), starts))
     return out
 
 
