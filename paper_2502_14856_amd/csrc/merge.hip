@@ -11,8 +11,10 @@ constexpr int kMergeWaves = 4;
 
 __global__ __launch_bounds__(kMergeWaves * kWave) void merge_kernel(Partials P, int G, int M, int k,
                                                                    int *token_ids, float *logp) {
-    const int m = blockIdx.x * kMergeWaves + (int)(threadIdx.x / kWave);
-    final_merge_all(P, G, m, M, M, k, token_ids, logp);   // one row per wavefront
+    __shared__ SelectScratch s_select[kMergeWaves];
+    const int wave = (int)(threadIdx.x / kWave);
+    const int m = blockIdx.x * kMergeWaves + wave;
+    final_merge_all(P, G, m, M, M, k, token_ids, logp, &s_select[wave]);   // one row per wavefront
 }
 
 }  // namespace

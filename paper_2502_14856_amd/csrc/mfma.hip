@@ -76,7 +76,8 @@ __global__ __launch_bounds__(kMfmaThreads) void mfma_kernel(MfmaArgs a) {
     float *run_ms = reinterpret_cast<float *>(base + L.ms_off);
     float *run_val = reinterpret_cast<float *>(base + L.val_off);
     int *run_id = reinterpret_cast<int *>(base + L.id_off);
-    __shared__ int s_is_last;
+    __shared__ int s_slot;
+    __shared__ SelectScratch s_select[kMfmaWaves];
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -209,10 +210,10 @@ __global__ __launch_bounds__(kMfmaThreads) void mfma_kernel(MfmaArgs a) {
                 };
                 if (p == (int)blockIdx.x)
                     block_fold_all<ZR, false>(mt * 16 + wave, kMfmaWaves, m_end, row_of, 1, 0, ids_lds,
-                                              n_valid, a.k);
+                                              n_valid, a.k, &s_select[wave]);
                 else
                     block_fold_all<ZR, true>(mt * 16 + wave, kMfmaWaves, m_end, row_of, 1, 0, ids_lds,
-                                             n_valid, a.k);
+                                             n_valid, a.k, &s_select[wave]);
             }
             __syncthreads();
         }
@@ -221,21 +222,26 @@ __global__ __launch_bounds__(kMfmaThreads) void mfma_kernel(MfmaArgs a) {
     if (a.sink == (int)Sink::kLogits || a.sink == (int)Sink::kStreamOnly) return;
 
     const int gidx = blockIdx.x, G = gridDim.x;
+    const Partials part = a.part;   // a local copy keeps the argument block itself in registers
     for (int m = wave; m < a.M; m += kMfmaWaves) {
         if (lane < a.k) {
-            publish(a.part.val + part_index(m * a.k + lane, gidx), run_val[m * a.k + lane]);
-            publish(a.part.id + part_index(m * a.k + lane, gidx), run_id[m * a.k + lane]);
+            publish(part.val + part_index(m * a.k + lane, gidx), run_val[m * a.k + lane]);
+            publish(part.id + part_index(m * a.k + lane, gidx), run_id[m * a.k + lane]);
         }
-        if (lane < 2) publish(a.part.ms + part_index(m * 2 + lane, gidx), run_ms[2 * m + lane]);
+        if (lane < 2) publish(part.ms + part_index(m * 2 + lane, gidx), run_ms[2 * m + lane]);
     }
     if (a.sink == (int)Sink::kPartialsOnly) return;
 
-    if (!arrive_is_last(a.ticket, G, &s_is_last)) return;
-    final_merge_all(a.part, G, wave, kMfmaWaves, a.M, a.k, a.token_ids, a.logp);
-    if (tid == 0) reset_ticket(a.ticket);   // leave the workspace ready for the next call
+    const Arrival ar{a.ticket, a.ticket + 1, a.ticket + 2};
+    const int R = merger_count(G, a.M);
+    const int r = arrive_and_wait(ar, G, R, &s_slot);
+    if (r < 0) return;
+    final_merge_all(part, G, r + R * wave, R * kMfmaWaves, a.M, a.k, a.token_ids, a.logp, &s_select[wave]);
+    merger_done(ar, R);
 }
 
 constexpr int kLdsBudget = 160 * 1024;
+constexpr int kStaticLdsReserve = 8 * 1024;   // room for the kernel's static LDS (selection scratch)
 constexpr int kRB = 2;
 constexpr int kPD = 3;
 constexpr int kZR = kMfmaWaves * kRB * 16;
@@ -247,7 +253,7 @@ fr_status launch_one(const MfmaArgs &a, int grid, int lds, hipStream_t s) {
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kLdsBudget - 64) != hipSuccess) {
+                                kLdsBudget - kStaticLdsReserve) != hipSuccess) {
             (void)hipGetLastError();
             return FR_ERR_HIP;
         }
@@ -270,7 +276,7 @@ int mt16_bucket(int M) {
 int mfma_max_rows(int k) {
     int best = 0;
     for (int mt : {1, 2, 4, 8, 12, 16})
-        if (MfmaLds(mt, kZR, k).total <= kLdsBudget - 1024) best = mt * 16;
+        if (MfmaLds(mt, kZR, k).total <= kLdsBudget - kStaticLdsReserve) best = mt * 16;
     return best;
 }
 
@@ -279,7 +285,7 @@ fr_status launch_mfma(const HeadProblem &p, Sink sink, const fr_tuning *t, hipSt
     const int MT16 = mt16_bucket(p.M);
     if (MT16 < 0) return FR_ERR_UNSUPPORTED;
     const int lds = MfmaLds(MT16, kZR, p.k).total;
-    if (lds > kLdsBudget - 1024) return FR_ERR_UNSUPPORTED;
+    if (lds > kLdsBudget - kStaticLdsReserve) return FR_ERR_UNSUPPORTED;
     const int cus = device_cu_count();
     if (cus <= 0) return FR_ERR_HIP;
 

@@ -55,6 +55,7 @@ struct SkinnyArgs {
     float *logp;
     float *z_out;
     int z_ld;
+    long long *trace;     // optional [gridDim.x][8] phase timestamps (100 MHz clock)
 };
 
 __host__ __device__ constexpr int round_up(int x, int m) { return (x + m - 1) / m * m; }
@@ -85,7 +86,8 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     float *run_ms = reinterpret_cast<float *>(base + L.ms_off);
     float *run_val = reinterpret_cast<float *>(base + L.val_off);
     int *run_id = reinterpret_cast<int *>(base + L.id_off);
-    __shared__ int s_is_last;
+    __shared__ int s_slot;
+    __shared__ SelectScratch s_select[WAVES];
 
     constexpr int ZR_MAX = WAVES * kTileRows;
     constexpr int kStep16 = kLanesAlongD;        // 16-byte chunks per row per step
@@ -100,6 +102,10 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     const int tile_in_pass = wave / KS;
     const int ks = wave - tile_in_pass * KS;
     const int G = gridDim.x;
+    auto stamp = [&](int slot) {
+        if (a.trace && tid == 0) a.trace[blockIdx.x * 8 + slot] = (long long)__builtin_amdgcn_s_memrealtime();
+    };
+    stamp(0);
 
     // Step range of this wavefront along d, split into a pipelined part (whole groups of
     // DEPTH full steps, no bounds handling at all) and leftovers (at most DEPTH - 1 steps,
@@ -160,6 +166,7 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
         run_ms[2 * tid + 1] = 0.0f;
     }
     __syncthreads();
+    stamp(1);
 
     for (; p < a.passes; p += G) {
         const int pass_row0 = p * ZR;
@@ -264,6 +271,7 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
                     z_lds[(ks * MT + m) * ZR + rl + r] = acc[r][m];
         }
         __syncthreads();
+        stamp(2);
 
         // ---- consume the pass ----
         if (a.sink == (int)Sink::kLogits) {
@@ -280,9 +288,9 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
                 return FoldRow{z_lds + m * ZR, run_ms + 2 * m, run_val + m * a.k, run_id + m * a.k};
             };
             if (p == (int)blockIdx.x)
-                block_fold_all<ZR_MAX, false>(wave, WAVES, a.M, row_of, KS, MT * ZR, ids_lds, n_valid, a.k);
+                block_fold_all<ZR_MAX, false>(wave, WAVES, a.M, row_of, KS, MT * ZR, ids_lds, n_valid, a.k, &s_select[wave]);
             else
-                block_fold_all<ZR_MAX, true>(wave, WAVES, a.M, row_of, KS, MT * ZR, ids_lds, n_valid, a.k);
+                block_fold_all<ZR_MAX, true>(wave, WAVES, a.M, row_of, KS, MT * ZR, ids_lds, n_valid, a.k, &s_select[wave]);
         }
         __syncthreads();
     }
@@ -290,25 +298,34 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     if (a.sink == (int)Sink::kLogits || a.sink == (int)Sink::kStreamOnly) return;
 
     // ---- publish this workgroup's partials ----
+    const Partials part = a.part;   // a local copy keeps the argument block itself in registers
+    stamp(3);
     const int g = blockIdx.x;
     for (int m = wave; m < a.M; m += WAVES) {
         if (lane < a.k) {
-            publish(a.part.val + part_index(m * a.k + lane, g), run_val[m * a.k + lane]);
-            publish(a.part.id + part_index(m * a.k + lane, g), run_id[m * a.k + lane]);
+            publish(part.val + part_index(m * a.k + lane, g), run_val[m * a.k + lane]);
+            publish(part.id + part_index(m * a.k + lane, g), run_id[m * a.k + lane]);
         }
-        if (lane < 2) publish(a.part.ms + part_index(m * 2 + lane, g), run_ms[2 * m + lane]);
+        if (lane < 2) publish(part.ms + part_index(m * 2 + lane, g), run_ms[2 * m + lane]);
     }
     if (a.sink == (int)Sink::kPartialsOnly) return;
 
     // ---- the last workgroup to arrive merges all partials (single launch) ----
-    if (!arrive_is_last(a.ticket, G, &s_is_last)) return;
-    final_merge_all(a.part, G, wave, WAVES, a.M, a.k, a.token_ids, a.logp);
-    if (tid == 0) reset_ticket(a.ticket);   // leave the workspace ready for the next call
+    const Arrival ar{a.ticket, a.ticket + 1, a.ticket + 2};
+    const int R = merger_count(G, a.M);
+    const int r = arrive_and_wait(ar, G, R, &s_slot);
+    stamp(4);
+    if (r < 0) return;
+    final_merge_all(part, G, r + R * wave, R * WAVES, a.M, a.k, a.token_ids, a.logp, &s_select[wave]);
+    merger_done(ar, R);
+    __syncthreads();
+    stamp(5);
 }
 
 // ---------------------------------------------------------------- host side ---
 
 constexpr int kLdsBudget = 160 * 1024;   // bytes of LDS per workgroup on gfx950
+constexpr int kStaticLdsReserve = 16 * 1024;   // room for the kernel's static LDS (selection scratch)
 
 constexpr int kMTBuckets[] = {1, 2, 4, 6, 8, 10, 12, 16};
 
@@ -325,7 +342,7 @@ fr_status launch_one(const SkinnyArgs &a, int grid, int lds, hipStream_t s) {
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kLdsBudget - 64) != hipSuccess) {
+                                kLdsBudget - kStaticLdsReserve) != hipSuccess) {
             (void)hipGetLastError();
             return FR_ERR_HIP;
         }
@@ -367,7 +384,7 @@ bool skinny_fits(int M, int d, int k) {
     const int MT = bucket_for(M);
     if (MT < 0) return false;
     const int steps = (d / 8 + kLanesAlongD - 1) / kLanesAlongD;
-    return SkinnyLds(MT, 16, steps, k).total <= kLdsBudget - 1024;
+    return SkinnyLds(MT, 16, steps, k).total <= kLdsBudget - kStaticLdsReserve;
 }
 
 fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hipStream_t s) {
@@ -418,6 +435,7 @@ fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hip
     a.logp = p.logp;
     a.z_out = p.z_out;
     a.z_ld = p.z_ld;
+    a.trace = t ? static_cast<long long *>(t->trace) : nullptr;
 
     int grid = a.passes < cus ? a.passes : cus;
     if (t && t->grid > 0) grid = t->grid < a.passes ? t->grid : a.passes;

@@ -70,6 +70,16 @@ __device__ __forceinline__ int wave_min_i32(int v) {
     return min(min(a, b), min(c, d));
 }
 
+__device__ __forceinline__ unsigned wave_min_u32(unsigned v) {
+    v = min(v, (unsigned)dpp_i32<kDppQuadXor1>((int)v));
+    v = min(v, (unsigned)dpp_i32<kDppQuadXor2>((int)v));
+    v = min(v, (unsigned)dpp_i32<kDppRowHalfMirror>((int)v));
+    v = min(v, (unsigned)dpp_i32<kDppRowMirror>((int)v));
+    unsigned a = __builtin_amdgcn_readlane(v, 0), b = __builtin_amdgcn_readlane(v, 16);
+    unsigned c = __builtin_amdgcn_readlane(v, 32), d = __builtin_amdgcn_readlane(v, 48);
+    return min(min(a, b), min(c, d));
+}
+
 // Sum over the 64 lanes in a fixed order, returned to every lane.
 __device__ __forceinline__ float wave_sum_f32(float v) {
     v += dpp_f32<kDppQuadXor1>(v);
@@ -90,6 +100,109 @@ __device__ __forceinline__ bool cand_before(float va, int ida, float vb, int idb
 // exp(a - b) that is 0 (not NaN) when a is -inf, whatever b is.
 __device__ __forceinline__ float exp_diff(float a, float b) {
     return (a == kNegInf) ? 0.0f : __expf(a - b);
+}
+
+// Candidate keys: 64 bits that order like (value descending, token id ascending) when
+// compared as unsigned integers, larger = better.  High word: the fp32 value mapped
+// monotonically to unsigned (-0 is folded into +0 first, as the float comparison does);
+// low word: ~id.  The all-zero key marks an empty slot (no finite or infinite value maps
+// to a zero high word).
+__device__ __forceinline__ unsigned key_hi_of(float v) {
+    const unsigned u = __builtin_bit_cast(unsigned, v + 0.0f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float value_of_key_hi(unsigned h) {
+    const unsigned u = (h & 0x80000000u) ? (h & 0x7FFFFFFFu) : ~h;
+    return __builtin_bit_cast(float, u);
+}
+__device__ __forceinline__ unsigned long long make_key(unsigned hi, unsigned lo) {
+    return ((unsigned long long)hi << 32) | lo;
+}
+
+// Per-wavefront LDS scratch of the threshold selection below.
+struct SelectScratch {
+    unsigned long long key[kWave];
+    int pl[kWave];
+};
+
+constexpr int kSmallKMax = 16;   // largest k the threshold selection handles
+
+/*
+ * The k best (k <= 16) of 64*CPL keyed candidates, without k dependent rounds:
+ *   1. each quad of lanes takes the maximum value of its 4*CPL candidates; the k-th
+ *      largest of the 16 quad maxima, L, is a lower bound of the k-th best value overall
+ *      (k different quads hold a value >= L);
+ *   2. the candidates with value >= L (at least k, a few more in expectation) are packed
+ *      into lanes 0..n-1 through LDS;
+ *   3. each survivor counts the survivors that beat it; that count is its rank.
+ * On return lane i < n holds one survivor (key, pl) and its rank; the k best are the
+ * survivors with rank < k.  Returns false, having decided nothing, if more than 64
+ * candidates survive (massively tied values): the caller then falls back to the
+ * round-by-round selection.
+ */
+#ifdef FRSPEC_SELECT_TRACE
+#define FRSPEC_SELECT_STAMP(i) \
+    do { if (lane_id() == 0) FRSPEC_SELECT_TRACE[i] = (long long)__builtin_readcyclecounter(); } while (0)
+#else
+#define FRSPEC_SELECT_STAMP(i) do { } while (0)
+#endif
+
+template <int CPL>
+__device__ __forceinline__ bool wave_topk_small(const unsigned (&hi)[CPL], const unsigned (&lo)[CPL],
+                                                const int (&pl)[CPL], int k, SelectScratch *sc,
+                                                unsigned long long &mine, int &mine_pl, int &rank,
+                                                int &n) {
+    const int lane = lane_id();
+    FRSPEC_SELECT_STAMP(0);
+    unsigned qm = hi[0];
+#pragma unroll
+    for (int c = 1; c < CPL; ++c) qm = max(qm, hi[c]);
+    qm = max(qm, (unsigned)dpp_i32<kDppQuadXor1>((int)qm));
+    qm = max(qm, (unsigned)dpp_i32<kDppQuadXor2>((int)qm));
+    int greater = 0;   // quads whose maximum is strictly larger than this lane's quad maximum
+#pragma unroll
+    for (int q = 0; q < 16; ++q) greater += (unsigned)__builtin_amdgcn_readlane((int)qm, 4 * q) > qm;
+    // the smallest quad maximum that still is among the k largest = the k-th largest
+    FRSPEC_SELECT_STAMP(1);
+    const unsigned L = wave_min_u32(greater <= k - 1 ? qm : 0xFFFFFFFFu);
+    FRSPEC_SELECT_STAMP(2);
+
+    n = 0;
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+        const bool sv = hi[c] != 0u && hi[c] >= L;
+        const unsigned long long mask = __ballot(sv);
+        const int pos = n + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32),
+                                                           __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u));
+        if (sv && pos < kWave) {
+            sc->key[pos] = make_key(hi[c], lo[c]);
+            sc->pl[pos] = pl[c];
+        }
+        n += (int)__popcll(mask);
+    }
+    FRSPEC_SELECT_STAMP(3);
+    if (n > kWave) return false;
+
+    mine = lane < n ? sc->key[lane] : 0ull;
+    mine_pl = lane < n ? sc->pl[lane] : -1;
+    rank = 0;
+    FRSPEC_SELECT_STAMP(4);
+    // every survivor is compared with every survivor; the keys are read back from LDS
+    // (same address in all lanes: a broadcast), several reads in flight at a time
+#pragma unroll 8
+    for (int j = 0; j < n; ++j) rank += sc->key[j] > mine;
+    FRSPEC_SELECT_STAMP(5);
+    return true;
+}
+
+// Rank of each lane's key among the keys of all 64 lanes (number of strictly larger keys);
+// empty lanes pass key 0.  For candidate sets that already sit one per lane.
+__device__ __forceinline__ int wave_rank_all(unsigned long long mine, SelectScratch *sc) {
+    sc->key[lane_id()] = mine;
+    int rank = 0;
+#pragma unroll 16
+    for (int j = 0; j < kWave; ++j) rank += sc->key[j] > mine;
+    return rank;
 }
 
 /*
