@@ -102,9 +102,9 @@ fr_status fr_workspace_init(void *workspace, size_t workspace_bytes, fr_stream s
  *   workspace       >= fr_workspace_bytes(M, d, V_sub, k) bytes, 16-byte aligned,
  *                   prepared by fr_workspace_init
  * Requires M >= 1, d % 8 == 0, 1 <= k <= min(V_sub, FR_K_MAX), V_sub < 2^31.
- * M <= 16 runs on the vector ALUs; larger M runs on the matrix cores in slabs of up to
- * 256 rows of H.  FR_ERR_UNSUPPORTED is returned if M <= 16 and d is so large that the
- * M rows of H do not fit the 160 KB of LDS together with the kernel's own state.
+ * M <= 16 runs in the skinny kernel (all of H resident in LDS, W streamed once through
+ * registers); larger M, or an H too large for LDS, runs in the chunked matrix-core kernel
+ * in slabs of up to 256 rows of H.
  * NaN or infinite inputs give unspecified outputs but never a fault or a hang.
  */
 fr_status fr_draft_topk(const void *H, int64_t M, int64_t d,
@@ -134,10 +134,12 @@ fr_status fr_draft_logits(const void *H, int64_t M, int64_t d,
  * A zero in any field means "library default".
  */
 typedef struct fr_tuning {
-    int32_t path;        /* 1 = vector-ALU skinny kernel, 2 = matrix-core kernel */
+    int32_t path;        /* 3 = skinny kernel (M <= 16), products on the matrix cores (default),
+                            1 = skinny kernel, products on the vector ALUs (bf16 dot2),
+                            2 = chunked matrix-core kernel (any M) */
     int32_t two_launch;  /* 1 = merge the per-workgroup partials in a second launch instead
                             of in the last workgroup to arrive (single launch) */
-    int32_t variant;     /* skinny kernel build variant (pipeline depth / waves), 0..FR_NUM_VARIANTS-1 mapped from 1.. */
+    int32_t variant;     /* skinny kernel build variant, 1-based (waves x pipeline depth x unit) */
     int32_t ksplit;      /* waves that share one 16-row tile along d (1, 2, 4, 8) */
     int32_t grid;        /* number of workgroups (<= 512) */
     int32_t stream_only; /* 1 = measurement only: run the contraction and drop the logits

@@ -58,7 +58,7 @@ fr_status head_topk(const void *H, int64_t M, int64_t d, const void *W, const in
     if (!aligned16(workspace)) return FR_ERR_ALIGNMENT;
     const WorkspaceLayout wl(M, k);
     if (workspace_bytes < wl.total) return FR_ERR_WORKSPACE;
-    if (tuning && (tuning->path < 0 || tuning->path > 2 || tuning->grid < 0 ||
+    if (tuning && (tuning->path < 0 || tuning->path > 3 || tuning->grid < 0 ||
                    tuning->grid > kWorkspaceGridMax || tuning->variant < 0 || tuning->ksplit < 0))
         return FR_ERR_INVALID_ARG;
 
@@ -75,12 +75,14 @@ fr_status head_topk(const void *H, int64_t M, int64_t d, const void *W, const in
     p.ws.part_id = reinterpret_cast<int *>(ws + wl.id_off);
     hipStream_t s = static_cast<hipStream_t>(stream);
 
+    // paths: 3 = skinny kernel on the matrix cores, 1 = skinny kernel on the vector ALUs,
+    // 2 = chunked matrix-core kernel (any M)
     int path = tuning ? tuning->path : 0;
-    if (path == 0) path = (M <= kSkinnyMaxM && skinny_fits((int)M, (int)d, k)) ? 1 : 2;
+    if (path == 0) path = (M <= kSkinnyMaxM && skinny_fits((int)M, (int)d, k)) ? 3 : 2;
     const bool two_launch = tuning && tuning->two_launch;
     const bool stream_only = tuning && tuning->stream_only;
 
-    if (path == 1) {
+    if (path == 1 || path == 3) {
         if (M > kSkinnyMaxM) return FR_ERR_UNSUPPORTED;
         p.H = H;
         p.M = static_cast<int>(M);

@@ -21,6 +21,8 @@ namespace frspec {
 namespace {
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float dot2_bf16(unsigned w, unsigned h, float acc) {
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w),
@@ -61,11 +63,16 @@ struct SkinnyArgs {
 __host__ __device__ constexpr int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
 // LDS carve-up, in bytes, identical on host and device.
+constexpr int kStagePitch16 = kLanesAlongD + 1;   // 272-byte rows: conflict-free fragment reads
+
 struct SkinnyLds {
-    int h_off, z_off, ids_off, ms_off, val_off, id_off, total;
-    __host__ __device__ SkinnyLds(int MT, int waves, int steps, int k) {
+    int h_off, stage_off, z_off, ids_off, ms_off, val_off, id_off, total;
+    // `hrows` rows of H are staged: all MT (zero padded) for the dot-product variant, whose
+    // register tiles are MT wide; only the M real ones for the matrix-core variant.
+    __host__ __device__ SkinnyLds(int MT, int hrows, int waves, int steps, int k, bool mfma) {
         int o = 0;
-        h_off = o;   o += MT * steps * kLanesAlongD * 16;
+        h_off = o;   o += hrows * steps * kLanesAlongD * 16;
+        stage_off = o; o += mfma ? waves * kTileRows * kStagePitch16 * 16 : 0;
         z_off = o;   o += (waves * kTileRows * MT + waves * kTileRows) * 4;
         ids_off = o; o += waves * kTileRows * 4;
         ms_off = o;  o += MT * 2 * 4;
@@ -75,12 +82,14 @@ struct SkinnyLds {
     }
 };
 
-template <int MT, int WAVES, int DEPTH>
+template <int MT, int WAVES, int DEPTH, bool MFMA>
 __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     extern __shared__ u32x4 smem[];
     char *base = reinterpret_cast<char *>(smem);
-    const SkinnyLds L(MT, WAVES, a.steps, a.k);
+    const int hrows = MFMA ? a.M : MT;
+    const SkinnyLds L(MT, hrows, WAVES, a.steps, a.k, MFMA);
     u32x4 *H_lds = reinterpret_cast<u32x4 *>(base + L.h_off);
+    u32x4 *stage_lds = reinterpret_cast<u32x4 *>(base + L.stage_off);
     float *z_lds = reinterpret_cast<float *>(base + L.z_off);
     int *ids_lds = reinterpret_cast<int *>(base + L.ids_off);
     float *run_ms = reinterpret_cast<float *>(base + L.ms_off);
@@ -150,8 +159,9 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
                 wb[u][r] = load_w(Wb, wo[r] + g_first * kGroupBytes + u * kStepBytes);
     }
 
-    // stage H (zero padded to MT rows and to whole steps) and reset the running state
-    for (int i = tid; i < MT * hpitch; i += WAVES * kWave) {
+    // stage H (zero padded to whole steps, and to MT rows where the tiles need it) and
+    // reset the running state
+    for (int i = tid; i < hrows * hpitch; i += WAVES * kWave) {
         const int m = i / hpitch, c = i - m * hpitch;
         u32x4 v = zero_u32x4();
         if (m < a.M && c < a.d8) v = a.H[(size_t)m * a.d8 + c];
@@ -176,32 +186,63 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
             ids_lds[tid] = a.idx_map ? a.idx_map[row] : row;
         }
 
-        float acc[kRowsPerLane][MT];
-#pragma unroll
-        for (int r = 0; r < kRowsPerLane; ++r)
-#pragma unroll
-            for (int m = 0; m < MT; ++m) acc[r][m] = 0.0f;
-
-        // one step: 16 bytes of each of the lane's 4 rows against the M rows of H
-        auto compute = [&](const u32x4 (&w)[kRowsPerLane], const u32x4 *hp) {
-            u32x4 h[MT];
-#pragma unroll
-            for (int m = 0; m < MT; ++m) h[m] = hp[m * hpitch];
+        // Accumulators.  Vector-ALU variant: the lane's share (16 bytes per step) of 4 rows x
+        // MT rows of H.  Matrix-core variant: one 16 x 16 tile, lane (j, g) = column m = j,
+        // rows 4g..4g+3.
+        float acc[MFMA ? 1 : kRowsPerLane][MFMA ? 1 : MT];
+        f32x4_t accm = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (!MFMA) {
 #pragma unroll
             for (int r = 0; r < kRowsPerLane; ++r)
 #pragma unroll
-                for (int m = 0; m < MT; ++m) {
-                    float t = acc[r][m];
-                    t = dot2_bf16(w[r].x, h[m].x, t);
-                    t = dot2_bf16(w[r].y, h[m].y, t);
-                    t = dot2_bf16(w[r].z, h[m].z, t);
-                    t = dot2_bf16(w[r].w, h[m].w, t);
-                    acc[r][m] = t;
+                for (int m = 0; m < MT; ++m) acc[r][m] = 0.0f;
+        }
+
+        // One step: 16 bytes of each of the lane's 4 rows (together the wavefront holds
+        // 16 rows x 128 elements) against the M rows of H.  `c0` is the index of the step's
+        // first 16-byte chunk along d.
+        auto compute = [&](const u32x4 (&w)[kRowsPerLane], int c0) {
+            if constexpr (MFMA) {
+                // Transpose through LDS into MFMA operand order: the loads deliver
+                // (row slot, 16-byte chunk) per lane, the A operand wants (row, 8-element
+                // group).  Only this wavefront touches its staging rows and LDS executes a
+                // wavefront's operations in order, so no barrier is needed.
+                u32x4 *st = stage_lds + wave * (kTileRows * kStagePitch16);
+#pragma unroll
+                for (int r = 0; r < kRowsPerLane; ++r)
+                    st[(rs * kRowsPerLane + r) * kStagePitch16 + lk] = w[r];
+                const int j = lk, g = rs;   // operand coordinates of this lane
+                const int hrow = j < a.M ? j : a.M - 1;   // columns >= M are never read back
+                bf16x8_t af[4], bf[4];
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    af[kk] = __builtin_bit_cast(bf16x8_t, st[j * kStagePitch16 + kk * 4 + g]);
+                    bf[kk] = __builtin_bit_cast(bf16x8_t, H_lds[hrow * hpitch + c0 + kk * 4 + g]);
                 }
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk)
+                    accm = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[kk], bf[kk], accm, 0, 0, 0);
+            } else {
+                const u32x4 *hp = H_lds + c0 + lk;
+                u32x4 h[MT];
+#pragma unroll
+                for (int m = 0; m < MT; ++m) h[m] = hp[m * hpitch];
+#pragma unroll
+                for (int r = 0; r < kRowsPerLane; ++r)
+#pragma unroll
+                    for (int m = 0; m < MT; ++m) {
+                        float t = acc[r][m];
+                        t = dot2_bf16(w[r].x, h[m].x, t);
+                        t = dot2_bf16(w[r].y, h[m].y, t);
+                        t = dot2_bf16(w[r].z, h[m].z, t);
+                        t = dot2_bf16(w[r].w, h[m].w, t);
+                        acc[r][m] = t;
+                    }
+            }
         };
 
         if (groups > 0) {
-            const u32x4 *hp0 = H_lds + s_begin * kStep16 + lk;
+            const int c_begin = s_begin * kStep16;
             int grp = g_first;
             // Steady state: consume stage u, then refill it with the same stage of the next
             // group.  The scheduling barriers keep the refill where it is written: left
@@ -209,11 +250,11 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
             // ranges) and the wavefront then waits for every load it has just issued.
             for (int it = 0; it < groups - 1; ++it) {
                 const int nxt = (grp + 1 == groups) ? 0 : grp + 1;
-                const u32x4 *hp = hp0 + grp * (DEPTH * kStep16);
+                const int cg = c_begin + grp * (DEPTH * kStep16);
                 const unsigned nofs = (unsigned)nxt * kGroupBytes;
 #pragma unroll
                 for (int u = 0; u < DEPTH; ++u) {
-                    compute(wb[u], hp + u * kStep16);
+                    compute(wb[u], cg + u * kStep16);
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int r = 0; r < kRowsPerLane; ++r)
@@ -223,14 +264,14 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
                 grp = nxt;
             }
             // drain; the stages freed here start on the next pass of this workgroup
-            const u32x4 *hp = hp0 + grp * (DEPTH * kStep16);
+            const int cg = c_begin + grp * (DEPTH * kStep16);
             const bool has_next = p + G < a.passes;
             if (has_next) {
                 row_offsets(p + G, wo);
                 const unsigned nofs = (unsigned)g_first * kGroupBytes;
 #pragma unroll
                 for (int u = 0; u < DEPTH; ++u) {
-                    compute(wb[u], hp + u * kStep16);
+                    compute(wb[u], cg + u * kStep16);
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int r = 0; r < kRowsPerLane; ++r)
@@ -239,7 +280,7 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
                 }
             } else {
 #pragma unroll
-                for (int u = 0; u < DEPTH; ++u) compute(wb[u], hp + u * kStep16);
+                for (int u = 0; u < DEPTH; ++u) compute(wb[u], cg + u * kStep16);
             }
         }
         if (s_pipe_end < s_end) {
@@ -253,22 +294,30 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
                 u32x4 w[kRowsPerLane];
 #pragma unroll
                 for (int r = 0; r < kRowsPerLane; ++r) w[r] = load_w(Wb, wr[r] + (unsigned)c * 16u);
-                compute(w, H_lds + s * kStep16 + lk);
+                compute(w, s * kStep16);
             }
         }
 
-        // sum the 16 lanes of each row slot; lane 0 of the slot stores the tile's logits
+        if constexpr (MFMA) {
+            // lane (j, g) owns rows 4g..4g+3 of column m = j
+            if (lk < a.M) {
+                float *dst = z_lds + (ks * MT + lk) * ZR + tile_in_pass * kTileRows + 4 * rs;
+                *reinterpret_cast<f32x4_t *>(dst) = accm;
+            }
+        } else {
+            // sum the 16 lanes of each row slot; lane 0 of the slot stores the tile's logits
 #pragma unroll
-        for (int r = 0; r < kRowsPerLane; ++r)
+            for (int r = 0; r < kRowsPerLane; ++r)
 #pragma unroll
-            for (int m = 0; m < MT; ++m) acc[r][m] = row16_sum(acc[r][m]);
-        if (lk == 0) {
-            const int rl = tile_in_pass * kTileRows + rs * kRowsPerLane;
+                for (int m = 0; m < MT; ++m) acc[r][m] = row16_sum(acc[r][m]);
+            if (lk == 0) {
+                const int rl = tile_in_pass * kTileRows + rs * kRowsPerLane;
 #pragma unroll
-            for (int m = 0; m < MT; ++m)
+                for (int m = 0; m < MT; ++m)
 #pragma unroll
-                for (int r = 0; r < kRowsPerLane; ++r)
-                    z_lds[(ks * MT + m) * ZR + rl + r] = acc[r][m];
+                    for (int r = 0; r < kRowsPerLane; ++r)
+                        z_lds[(ks * MT + m) * ZR + rl + r] = acc[r][m];
+            }
         }
         __syncthreads();
         stamp(2);
@@ -335,9 +384,9 @@ int bucket_for(int M) {
     return -1;
 }
 
-template <int MT, int WAVES, int DEPTH>
+template <int MT, int WAVES, int DEPTH, bool MFMA>
 fr_status launch_one(const SkinnyArgs &a, int grid, int lds, hipStream_t s) {
-    auto kern = skinny_kernel<MT, WAVES, DEPTH>;
+    auto kern = skinny_kernel<MT, WAVES, DEPTH, MFMA>;
     static bool attr_done = false;   // raising the dynamic LDS limit is idempotent
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -352,49 +401,79 @@ fr_status launch_one(const SkinnyArgs &a, int grid, int lds, hipStream_t s) {
     return hip_status(hipGetLastError());
 }
 
+// The dot-product variant is compiled per width of its register tile.
 template <int WAVES, int DEPTH>
-fr_status launch_mt(int MT, const SkinnyArgs &a, int grid, int lds, hipStream_t s) {
+fr_status launch_dot(int MT, const SkinnyArgs &a, int grid, int lds, hipStream_t s) {
     switch (MT) {
-        case 1: return launch_one<1, WAVES, DEPTH>(a, grid, lds, s);
-        case 2: return launch_one<2, WAVES, DEPTH>(a, grid, lds, s);
-        case 4: return launch_one<4, WAVES, DEPTH>(a, grid, lds, s);
-        case 6: return launch_one<6, WAVES, DEPTH>(a, grid, lds, s);
-        case 8: return launch_one<8, WAVES, DEPTH>(a, grid, lds, s);
-        case 10: return launch_one<10, WAVES, DEPTH>(a, grid, lds, s);
-        case 12: return launch_one<12, WAVES, DEPTH>(a, grid, lds, s);
-        case 16: return launch_one<16, WAVES, DEPTH>(a, grid, lds, s);
+        case 1: return launch_one<1, WAVES, DEPTH, false>(a, grid, lds, s);
+        case 2: return launch_one<2, WAVES, DEPTH, false>(a, grid, lds, s);
+        case 4: return launch_one<4, WAVES, DEPTH, false>(a, grid, lds, s);
+        case 6: return launch_one<6, WAVES, DEPTH, false>(a, grid, lds, s);
+        case 8: return launch_one<8, WAVES, DEPTH, false>(a, grid, lds, s);
+        case 10: return launch_one<10, WAVES, DEPTH, false>(a, grid, lds, s);
+        case 12: return launch_one<12, WAVES, DEPTH, false>(a, grid, lds, s);
+        case 16: return launch_one<16, WAVES, DEPTH, false>(a, grid, lds, s);
     }
     return FR_ERR_UNSUPPORTED;
 }
 
 struct Variant {
     int waves, depth;
+    bool mfma;
 };
-// Build variants (waves per workgroup, pipeline depth).  Variant 0 is what the library
-// uses; the others exist to measure the design space.  With 16 rows of H the accumulators
-// leave room for only two stages of W in the 256 registers of a lane.
-constexpr Variant kVariants[] = {{8, 4}, {8, 2}, {8, 3}, {8, 6}, {16, 2}};
+// Build variants: waves per workgroup, pipeline depth, and whether the products run on
+// the matrix cores or on the packed-bf16 dot instruction of the vector ALUs.  The matrix
+// cores win at every M on this chip (the dot instruction issues at about 70% of the plain
+// FMA rate and its work competes with the address arithmetic of the stream), so they are
+// the default; the vector-ALU build is kept as the measured alternative.
+//   0  matrix cores, 8 waves, 4 stages        (default)
+//   1  matrix cores, 4 waves, 8 stages        (default when H is too large for 8 staging rows)
+//   2  matrix cores, 8 waves, 3 stages
+//   3  matrix cores, 8 waves, 6 stages
+//   4  vector ALUs, 8 waves, 4 stages (2 stages when more than 10 rows of H: registers)
+//   5  vector ALUs, 8 waves, 3 stages
+constexpr Variant kVariants[] = {{8, 4, true}, {4, 8, true}, {8, 3, true},
+                                 {8, 6, true}, {8, 4, false}, {8, 3, false}};
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
+constexpr int kMfmaTile = 16;   // the matrix-core variant is compiled once, for up to 16 rows
 
-int default_variant(int MT) { return MT > 10 ? 1 : 0; }
+int lds_bytes(int M, int d, int k, int variant) {
+    const int steps = (d / 8 + kLanesAlongD - 1) / kLanesAlongD;
+    const Variant &v = kVariants[variant];
+    const int MT = v.mfma ? kMfmaTile : bucket_for(M);
+    return SkinnyLds(MT, v.mfma ? M : MT, v.waves, steps, k, v.mfma).total;
+}
+
+bool variant_fits(int M, int d, int k, int variant) {
+    return lds_bytes(M, d, k, variant) <= kLdsBudget - kStaticLdsReserve;
+}
+
+// -1 if no build of the skinny kernel can hold this problem's H in LDS
+int default_variant(int M, int d, int k, bool vector_alu) {
+    if (vector_alu) return variant_fits(M, d, k, 4) ? 4 : -1;
+    if (variant_fits(M, d, k, 0)) return 0;
+    if (variant_fits(M, d, k, 1)) return 1;
+    return -1;
+}
 
 }  // namespace
 
 bool skinny_fits(int M, int d, int k) {
-    const int MT = bucket_for(M);
-    if (MT < 0) return false;
-    const int steps = (d / 8 + kLanesAlongD - 1) / kLanesAlongD;
-    return SkinnyLds(MT, 16, steps, k).total <= kLdsBudget - kStaticLdsReserve;
+    return M <= kSkinnyMaxM && default_variant(M, d, k, false) >= 0;
 }
 
 fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hipStream_t s) {
-    const int MT = bucket_for(p.M);
-    if (MT < 0 || !skinny_fits(p.M, p.d, p.k)) return FR_ERR_UNSUPPORTED;
-    int variant = default_variant(MT);
+    if (p.M > kSkinnyMaxM) return FR_ERR_UNSUPPORTED;
+    const bool vector_alu = t && t->path == 1;
+    int variant = default_variant(p.M, p.d, p.k, vector_alu);
     if (t && t->variant > 0) {
         if (t->variant > kNumVariants) return FR_ERR_INVALID_ARG;
         variant = t->variant - 1;
+        if (!variant_fits(p.M, p.d, p.k, variant)) return FR_ERR_UNSUPPORTED;
     }
+    if (variant < 0) return FR_ERR_UNSUPPORTED;
+    const bool mfma = kVariants[variant].mfma;
+    const int MT = mfma ? kMfmaTile : bucket_for(p.M);
     const int waves = kVariants[variant].waves;
     const int cus = device_cu_count();
     if (cus <= 0) return FR_ERR_HIP;
@@ -440,15 +519,16 @@ fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hip
     int grid = a.passes < cus ? a.passes : cus;
     if (t && t->grid > 0) grid = t->grid < a.passes ? t->grid : a.passes;
     if (grid > kGridMax) grid = kGridMax;
-    const int lds = SkinnyLds(MT, waves, a.steps, p.k).total;
+    const int lds = lds_bytes(p.M, p.d, p.k, variant);
 
     fr_status st;
     switch (variant) {
-        case 0: st = launch_mt<8, 4>(MT, a, grid, lds, s); break;
-        case 1: st = launch_mt<8, 2>(MT, a, grid, lds, s); break;
-        case 2: st = launch_mt<8, 3>(MT, a, grid, lds, s); break;
-        case 3: st = launch_mt<8, 6>(MT, a, grid, lds, s); break;
-        case 4: st = launch_mt<16, 2>(MT, a, grid, lds, s); break;
+        case 0: st = launch_one<kMfmaTile, 8, 4, true>(a, grid, lds, s); break;
+        case 1: st = launch_one<kMfmaTile, 4, 8, true>(a, grid, lds, s); break;
+        case 2: st = launch_one<kMfmaTile, 8, 3, true>(a, grid, lds, s); break;
+        case 3: st = launch_one<kMfmaTile, 8, 6, true>(a, grid, lds, s); break;
+        case 4: st = MT > 10 ? launch_dot<8, 2>(MT, a, grid, lds, s) : launch_dot<8, 4>(MT, a, grid, lds, s); break;
+        case 5: st = launch_dot<8, 3>(MT, a, grid, lds, s); break;
         default: return FR_ERR_INVALID_ARG;
     }
     if (st != FR_OK) return st;

@@ -155,7 +155,11 @@ def test_draft_topk_skinny(M, d, V, V_sub, k):
     _say("draft skinny", M, d, V, V_sub, k)
     W, H, r = _case(V, d, M, 5)
     frac, _, _ = _run_draft(W, H, r, V_sub, k)
-    _say("  rows identical to the oracle:", frac)
+    _say("  rows identical to the oracle (matrix cores):", frac)
+    t = Tuning()
+    t.path = 1
+    frac, _, _ = _run_draft(W, H, r, V_sub, k, tuning=t)
+    _say("  rows identical to the oracle (vector ALUs):", frac)
 
 
 @pytest.mark.parametrize("M,d,V,V_sub,k", [
@@ -194,7 +198,8 @@ def test_duplicate_rows_tie_goes_to_lower_full_vocab_id():
 
 @pytest.mark.parametrize("knobs", [dict(two_launch=1), dict(ksplit=2), dict(ksplit=8), dict(grid=3),
                                    dict(grid=1), dict(variant=2), dict(variant=3), dict(variant=4),
-                                   dict(variant=5), dict(path=2), dict(path=2, two_launch=1)])
+                                   dict(variant=5), dict(variant=6), dict(path=1), dict(path=1, ksplit=4),
+                                   dict(path=1, two_launch=1), dict(path=2), dict(path=2, two_launch=1)])
 def test_kernel_variants_agree(knobs):
     _say("variants", knobs)
     W, H, r = _case(6000, 512, 10, 9)
