@@ -1,17 +1,24 @@
-// Vector-ALU kernel for a handful of H rows (M <= 16): the streaming skinny product of
-// Eq. 4 fused with the online log-softmax, the per-row top-k and the id remap.
+// Skinny kernel for a handful of H rows (M <= 16): the streaming product of Eq. 4 fused
+// with the online log-softmax, the per-row top-k and the id remap.
 //
 // The product is bound by reading W once from HBM (2*d bytes per vocabulary row against
 // 2*M*d flops), so the kernel is organised around the stream of W:
 //   * one persistent workgroup per compute unit keeps all M rows of H in LDS;
 //   * a wavefront owns a tile of 16 vocabulary rows.  Its 64 lanes form 4 row slots of
 //     16 lanes; a slot walks along d, each lane loading 16 bytes (8 bf16) of W per step,
-//     so one load instruction fetches 256 contiguous bytes from each of 4 rows.  Every
-//     lane serves 4 rows, which lets one 16-byte LDS read of H feed 4 rows of W;
-//   * W goes straight from HBM to registers through a software pipeline of DEPTH steps;
-//     products use the packed bf16 dot instruction with fp32 accumulation;
-//   * after the last step the 16 lanes of a slot are summed with DPP rotations; the
-//     tile's logits go to LDS, never to HBM.
+//     so one load instruction fetches 256 contiguous bytes from each of 4 rows (measured:
+//     64-byte pieces per row, which would suit the matrix cores directly, stream 10%
+//     slower);
+//   * W goes straight from HBM to registers through a software pipeline of DEPTH steps,
+//     every wavefront starting at a different column (see g_first);
+//   * the products of a step run either on the matrix cores (default): the 16 x 128 slab
+//     is transposed through a per-wavefront LDS buffer into MFMA operand order and
+//     multiplied with 4 x v_mfma_f32_16x16x32_bf16 against H taken from LDS; or on the
+//     vector ALUs: packed bf16 dot products with fp32 accumulation in a 4-row x MT
+//     register tile, summed over the 16 lanes of a slot with DPP rotations at the end;
+//   * the tile's logits go to LDS, never to HBM, and are folded into the workgroup's
+//     running (max, sum-exp, top-k) state; the last workgroups to arrive merge the
+//     partials of all workgroups and write the outputs.
 // For small vocabularies several wavefronts share a tile and split d between them
 // (KS > 1) so that every compute unit still has enough loads in flight.
 #include "epilogue.hpp"
@@ -149,7 +156,8 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     // W is requested before anything else so that HBM is busy while H is staged
     u32x4 wb[DEPTH][kRowsPerLane];
     unsigned wo[kRowsPerLane];
-    int p = blockIdx.x;
+    const int first_pass = (int)blockIdx.x;
+    int p = first_pass;
     if (p < a.passes && groups > 0) {
         row_offsets(p, wo);
 #pragma unroll
@@ -336,7 +344,7 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
             auto row_of = [&](int m) {
                 return FoldRow{z_lds + m * ZR, run_ms + 2 * m, run_val + m * a.k, run_id + m * a.k};
             };
-            if (p == (int)blockIdx.x)
+            if (p == first_pass)
                 block_fold_all<ZR_MAX, false>(wave, WAVES, a.M, row_of, KS, MT * ZR, ids_lds, n_valid, a.k, &s_select[wave]);
             else
                 block_fold_all<ZR_MAX, true>(wave, WAVES, a.M, row_of, KS, MT * ZR, ids_lds, n_valid, a.k, &s_select[wave]);

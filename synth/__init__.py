@@ -11,6 +11,7 @@ from .gen import (  # noqa: F401
     BASE_SEED,
     CONFIGS,
     DraftHeadConfig,
+    SWEEP_V_SUB,
     bf16_bits_to_f32,
     f32_to_bf16_bits,
     make_exact_case,
