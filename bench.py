@@ -34,7 +34,7 @@ N_COPIES = 5                # 5 x 256 MiB of W_sub > 256 MB memory-side cache
 
 def _profile_traffic():
     """HBM bytes per launch from the committed rocprofv3 counter summary, if present."""
-    path = os.path.join(ROOT, "profiles", "skinny_llama3_8b_pmc.txt")
+    path = os.path.join(ROOT, "profiles", "skinny_kernel_llama3_8b_pmc.txt")
     try:
         text = open(path).read()
     except OSError:
@@ -183,7 +183,7 @@ def main() -> int:
                    "d": d, "V": V, "V_sub": V_sub, "M": M, "k": k},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                      "frac": achieved / PEAK_HBM_GBPS, "traffic": traffic,
-                     "kernel": "skinny_kernel<10,8,4> (one launch per call)",
+                     "kernel": "skinny_kernel<16,8,4,true> (matrix-core build, one launch per call)",
                      "algorithmic_bytes_per_launch": bytes_per_call},
         "cpu_baseline": cpu,
         "extra": {
