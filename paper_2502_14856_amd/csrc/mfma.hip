@@ -1,18 +1,19 @@
-// Matrix-core kernel for many H rows (16 < M <= 256): Eq. 4 as a dense contraction
+// Wide kernel for many H rows (16 < M <= 256): Eq. 4 as a dense contraction
 // [V_rows x d] x [d x M] on v_mfma_f32_16x16x32_bf16, fused with the same online
 // log-softmax / top-k / remap epilogue as the skinny kernel.
 //
-//   * W is the streamed operand: each wavefront owns RB blocks of 16 vocabulary rows and
-//     loads its MFMA A fragments straight from HBM into registers (every byte of W is
-//     loaded by exactly one wavefront, once), PD chunks of 64 elements ahead;
-//   * H is the reused operand: the workgroup stages it through LDS in chunks of 64
-//     elements (double buffered), and every wavefront reads its B fragments from there;
-//   * inside a 64-element chunk lane group g (= lane / 16) takes elements
-//     [16g, 16g + 16): two 16-byte loads that are adjacent in memory, so the four groups
-//     cover a 128-byte line of each row.  The contraction does not care about the order
-//     of d as long as W and H agree, and both use this mapping;
+//   * W is the streamed operand and is read exactly once, with the load pattern that
+//     streams best (one instruction = 4 rows x 256 contiguous bytes, a register pipeline
+//     of DEPTH steps, every workgroup starting at a different column).  A wavefront owns
+//     RB blocks of 16 vocabulary rows; each 16 x 128 slab is transposed through a
+//     per-wavefront LDS buffer into MFMA operand order;
+//   * H is the reused operand and no longer fits LDS as a whole: the workgroup stages it
+//     in chunks of HCH x 64 elements of d (double buffered, one barrier per chunk), and
+//     every wavefront reads its B fragments from there;
 //   * accumulators hold z[16 rows x 16 m] per (row block, m tile): lane (j, g) owns rows
 //     4g..4g+3 of column m = j.
+// Three builds: 8 wavefronts x 16 rows for M <= 64 (bound by HBM), 4 wavefronts x 32 rows
+// for M <= 128 and M <= 256 (matrix cores and LDS close to the HBM stream).
 #include "epilogue.hpp"
 #include "internal.hpp"
 
@@ -21,20 +22,23 @@ namespace {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef const __attribute__((address_space(1))) char *GlobalBytes;
+typedef const __attribute__((address_space(1))) u32x4 *GlobalVec;
+__device__ __forceinline__ u32x4 load_w(GlobalBytes base, unsigned byte_offset) {
+    return __builtin_nontemporal_load(reinterpret_cast<GlobalVec>(base + byte_offset));
+}
 
-constexpr int kMfmaWaves = 4;
-constexpr int kMfmaThreads = kMfmaWaves * kWave;
-constexpr int kChunkElems = 64;           // elements of d per LDS stage
-constexpr int kChunk16 = kChunkElems / 8; // 16-byte units per row per stage
-constexpr int kHPitch16 = kChunk16 + 1;   // padded LDS pitch (144 bytes): conflict-free B reads
+constexpr int kStep16 = 16;                    // 16-byte chunks of d per step (128 elements)
+constexpr int kStagePitch16 = kStep16 + 1;     // 272-byte staging rows
 constexpr int kZPad = 4;
+constexpr int kZR = 128;                       // vocabulary rows per pass, all builds
 
-struct MfmaArgs {
+struct WideArgs {
     const u32x4 *H;
     const u32x4 *W;
     const int *idx_map;
     int M, d8, V_rows, k;
-    int chunks;   // ceil(d8 / 8)
+    int steps;    // ceil(d8 / 16)
     int passes;
     int sink;
     Partials part;
@@ -45,185 +49,260 @@ struct MfmaArgs {
     int z_ld;
 };
 
-__host__ __device__ constexpr int mfma_round_up(int x, int m) { return (x + m - 1) / m * m; }
+__host__ __device__ constexpr int wide_round_up(int x, int m) { return (x + m - 1) / m * m; }
 
-struct MfmaLds {
-    int h_off, z_off, ids_off, ms_off, val_off, id_off, total;
-    __host__ __device__ MfmaLds(int MT16, int ZR, int k) {
+struct WideLds {
+    int h_off, stage_off, z_off, ids_off, ms_off, val_off, id_off, total;
+    __host__ __device__ WideLds(int MT16, int HCH, int k) {
         const int Mp = MT16 * 16;
         int o = 0;
-        h_off = o;   o += 2 * Mp * kHPitch16 * 16;
-        z_off = o;   o += 16 * (ZR + kZPad) * 4;
-        ids_off = o; o += ZR * 4;
-        ms_off = o;  o += Mp * 2 * 4;
-        val_off = o; o += Mp * k * 4;
-        id_off = o;  o += Mp * k * 4;
-        total = mfma_round_up(o, 16);
+        h_off = o;     o += 2 * Mp * (HCH * 8 + 1) * 16;
+        stage_off = o; o += kZR * kStagePitch16 * 16;
+        z_off = o;     o += 16 * (kZR + kZPad) * 4;
+        ids_off = o;   o += kZR * 4;
+        ms_off = o;    o += Mp * 2 * 4;
+        val_off = o;   o += Mp * k * 4;
+        id_off = o;    o += Mp * k * 4;
+        total = wide_round_up(o, 16);
     }
 };
 
-template <int MT16, int RB, int PD>
-__global__ __launch_bounds__(kMfmaThreads) void mfma_kernel(MfmaArgs a) {
+template <int MT16, int RB, int WAVES, int DEPTH, int HCH>
+__global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
+    static_assert(WAVES * RB * 16 == kZR, "a pass is 128 vocabulary rows");
+    static_assert((2 * DEPTH) % HCH == 0, "groups of steps start on an H chunk boundary");
     constexpr int Mp = MT16 * 16;
-    constexpr int ZR = kMfmaWaves * RB * 16;   // vocabulary rows per pass
-    constexpr int kHLoads = (Mp * kChunk16 + kMfmaThreads - 1) / kMfmaThreads;
+    constexpr int NT = WAVES * kWave;
+    constexpr int HP = HCH * 8 + 1;                        // H chunk pitch in 16-byte units
+    constexpr int kHLoads = (Mp * HCH * 8 + NT - 1) / NT;  // 16-byte loads per thread per chunk
+    constexpr int kRowsPerLane = 4;
+    constexpr unsigned kStepBytes = kStep16 * 16;
     extern __shared__ u32x4 smem[];
     char *base = reinterpret_cast<char *>(smem);
-    const MfmaLds L(MT16, ZR, a.k);
+    const WideLds L(MT16, HCH, a.k);
     u32x4 *H_lds = reinterpret_cast<u32x4 *>(base + L.h_off);
+    u32x4 *stage_lds = reinterpret_cast<u32x4 *>(base + L.stage_off);
     float *z_stage = reinterpret_cast<float *>(base + L.z_off);
     int *ids_lds = reinterpret_cast<int *>(base + L.ids_off);
     float *run_ms = reinterpret_cast<float *>(base + L.ms_off);
     float *run_val = reinterpret_cast<float *>(base + L.val_off);
     int *run_id = reinterpret_cast<int *>(base + L.id_off);
     __shared__ int s_slot;
-    __shared__ SelectScratch s_select[kMfmaWaves];
+    __shared__ SelectScratch s_select[WAVES];
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
-    const int wave = tid / kWave;
-    const int j = lane & 15;   // A: row inside the 16-row block; B and D: column m
-    const int g = lane >> 4;   // A, B: 16-element group of the chunk; D: rows 4g..4g+3
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int lk = lane & 15, rs = lane >> 4;   // load layout: 16-byte chunk, row slot
+    const int j = lk, g = rs;                   // operand layout: row / column, k group
+    const int G = gridDim.x;
 
-    for (int i = tid; i < Mp * a.k; i += kMfmaThreads) {
+    for (int i = tid; i < Mp * a.k; i += NT) {
         run_val[i] = kNegInf;
         run_id[i] = INT_MAX;
     }
-    for (int i = tid; i < Mp; i += kMfmaThreads) {
+    for (int i = tid; i < Mp; i += NT) {
         run_ms[2 * i] = kNegInf;
         run_ms[2 * i + 1] = 0.0f;
     }
 
-    // global -> register half of the H staging: element (row, c16) of a chunk
+    // Order in which the steps along d are visited: whole groups of DEPTH full steps,
+    // cyclically from a group that differs per workgroup (all workgroups advance at the
+    // same pace; see the skinny kernel), then the leftover steps.
+    const int full_steps = a.d8 / kStep16;
+    const int groups = full_steps / DEPTH;
+    const int np = groups * DEPTH;
+    const int g_first = groups > 0 ? (int)(blockIdx.x % (unsigned)groups) : 0;
+    auto step_at = [&](int i) {
+        if (i >= np) return i;
+        int s = g_first * DEPTH + i;
+        return s >= np ? s - np : s;
+    };
+
+    // H chunk c = elements [c * HCH * 64, (c + 1) * HCH * 64) of d, all Mp rows (zero padded)
     u32x4 hreg[kHLoads];
-    auto h_fetch = [&](int chunk) {
+    auto h_fetch = [&](int c) {
 #pragma unroll
         for (int u = 0; u < kHLoads; ++u) {
-            const int e = tid + u * kMfmaThreads;
-            const int row = e / kChunk16, c16 = e - row * kChunk16;
-            const int col = chunk * kChunk16 + c16;
+            const int e = tid + u * NT;
+            const int row = e / (HCH * 8), c16 = e - row * (HCH * 8);
+            const int col = c * (HCH * 8) + c16;
             u32x4 v = zero_u32x4();
-            if (e < Mp * kChunk16 && row < a.M && col < a.d8) v = a.H[(size_t)row * a.d8 + col];
+            if (e < Mp * HCH * 8 && row < a.M && col < a.d8) v = a.H[(size_t)row * a.d8 + col];
             hreg[u] = v;
         }
     };
     auto h_store = [&](int buf) {
 #pragma unroll
         for (int u = 0; u < kHLoads; ++u) {
-            const int e = tid + u * kMfmaThreads;
-            const int row = e / kChunk16, c16 = e - row * kChunk16;
-            if (e < Mp * kChunk16) H_lds[(buf * Mp + row) * kHPitch16 + c16] = hreg[u];
+            const int e = tid + u * NT;
+            const int row = e / (HCH * 8), c16 = e - row * (HCH * 8);
+            if (e < Mp * HCH * 8) H_lds[(buf * Mp + row) * HP + c16] = hreg[u];
         }
     };
 
-    for (int p = blockIdx.x; p < a.passes; p += gridDim.x) {
-        const int pass_row0 = p * ZR;
-        const int n_valid = min(ZR, a.V_rows - pass_row0);
-        __syncthreads();   // previous pass has finished with ids_lds, z_stage and H_lds
+    const GlobalBytes Wb = (GlobalBytes)a.W;
+    auto row_offsets = [&](int pass, unsigned (&wo)[RB][kRowsPerLane]) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int r = 0; r < kRowsPerLane; ++r) {
+                const int row = min(pass * kZR + (wave * RB + rb) * 16 + rs * kRowsPerLane + r, a.V_rows - 1);
+                wo[rb][r] = ((unsigned)row * (unsigned)a.d8 + (unsigned)lk) * 16u;
+            }
+    };
+    u32x4 wb[DEPTH][RB][kRowsPerLane];
+    unsigned wo[RB][kRowsPerLane];
+    auto w_issue = [&](int u, int s) {   // full step s, no bounds handling
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int r = 0; r < kRowsPerLane; ++r)
+                wb[u][rb][r] = load_w(Wb, wo[rb][r] + (unsigned)s * kStepBytes);
+    };
+
+    int p = blockIdx.x;
+    if (p < a.passes && groups > 0) {
+        row_offsets(p, wo);
+#pragma unroll
+        for (int u = 0; u < DEPTH; ++u) w_issue(u, step_at(u));
+    }
+
+    for (; p < a.passes; p += G) {
+        const int pass_row0 = p * kZR;
+        const int n_valid = min(kZR, a.V_rows - pass_row0);
+        __syncthreads();   // the previous pass is done with ids_lds, z_stage and the H buffers
         if (tid < n_valid) {
             const int row = pass_row0 + tid;
             ids_lds[tid] = a.idx_map ? a.idx_map[row] : row;
         }
+        h_fetch((2 * step_at(0)) / HCH);
+        h_store(0);
 
-        const u32x4 *wrow[RB];
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-            const int row = min(pass_row0 + (wave * RB + rb) * 16 + j, a.V_rows - 1);
-            wrow[rb] = a.W + (size_t)row * a.d8;
-        }
         f32x4_t acc[RB][MT16];
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
             for (int mt = 0; mt < MT16; ++mt) acc[rb][mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-        u32x4 wreg[PD][RB][2];
-        // Past the end of a row the chunk index is clamped: the bytes are valid finite
-        // weights and the matching H entries staged in LDS are zero.
-        auto w_issue = [&](int slot, int chunk) {
+        // Step number i of the visiting order; its 16 x 128 slab(s) of W are in `w`.  The two
+        // halves of a step may lie in different H chunks.
+        bool have_next = false;
+        auto process_step = [&](int i, const u32x4 (&w)[RB][kRowsPerLane]) {
+            bf16x8_t af[RB][4];
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-                for (int kk = 0; kk < 2; ++kk) {
-                    const int c16 = min(chunk * kChunk16 + g * 2 + kk, a.d8 - 1);
-                    wreg[slot][rb][kk] = __builtin_nontemporal_load(wrow[rb] + c16);
+            for (int hs = 0; hs < 2; ++hs) {
+                const int h = 2 * i + hs;          // half-step number in visiting order
+                const int sub = h % HCH;           // its place inside the current H chunk
+                const int buf = (h / HCH) & 1;
+                if (sub == 0) {
+                    __syncthreads();               // the chunk in `buf` is complete; the other buffer is free
+                    const int h2 = h + HCH;
+                    have_next = h2 < 2 * a.steps;
+                    if (have_next) h_fetch((2 * step_at(h2 >> 1) + (h2 & 1)) / HCH);
                 }
-        };
+                if (hs == 0) {
+                    // transpose the slab into operand order through this wavefront's staging rows
+                    u32x4 *st = stage_lds + wave * (RB * 16 * kStagePitch16);
 #pragma unroll
-        for (int u = 0; u < PD; ++u)
-            if (u < a.chunks) w_issue(u, u);
-        h_fetch(0);
-        h_store(0);
-        __syncthreads();
-
-        for (int c0 = 0; c0 < a.chunks; c0 += PD) {
+                    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-            for (int u = 0; u < PD; ++u) {
-                const int c = c0 + u;
-                if (c < a.chunks) {
-                    const int cur = c & 1;
-                    if (c + 1 < a.chunks) h_fetch(c + 1);
+                        for (int r = 0; r < kRowsPerLane; ++r)
+                            st[(rb * 16 + rs * kRowsPerLane + r) * kStagePitch16 + lk] = w[rb][r];
 #pragma unroll
-                    for (int kk = 0; kk < 2; ++kk) {
-                        bf16x8_t bfrag[MT16];
+                    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-                        for (int mt = 0; mt < MT16; ++mt)
-                            bfrag[mt] = __builtin_bit_cast(
-                                bf16x8_t, H_lds[(cur * Mp + mt * 16 + j) * kHPitch16 + g * 2 + kk]);
+                        for (int kk = 0; kk < 4; ++kk)
+                            af[rb][kk] = __builtin_bit_cast(bf16x8_t, st[(rb * 16 + j) * kStagePitch16 + kk * 4 + g]);
+                }
 #pragma unroll
-                        for (int rb = 0; rb < RB; ++rb) {
-                            const bf16x8_t afrag = __builtin_bit_cast(bf16x8_t, wreg[u][rb][kk]);
+                for (int kk2 = 0; kk2 < 2; ++kk2) {
 #pragma unroll
-                            for (int mt = 0; mt < MT16; ++mt)
-                                acc[rb][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                    afrag, bfrag[mt], acc[rb][mt], 0, 0, 0);
-                        }
+                    for (int mt = 0; mt < MT16; ++mt) {
+                        const bf16x8_t bf = __builtin_bit_cast(
+                            bf16x8_t, H_lds[(buf * Mp + mt * 16 + j) * HP + sub * 8 + kk2 * 4 + g]);
+#pragma unroll
+                        for (int rb = 0; rb < RB; ++rb)
+                            acc[rb][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[rb][2 * hs + kk2], bf,
+                                                                                  acc[rb][mt], 0, 0, 0);
                     }
-                    if (c + PD < a.chunks) w_issue(u, c + PD);
-                    if (c + 1 < a.chunks) h_store(cur ^ 1);
-                    __syncthreads();
                 }
+                if (sub == HCH - 1 && have_next) h_store(buf ^ 1);
+            }
+        };
+
+        int i = 0;
+        for (int grp = 0; grp < groups; ++grp) {
+            const bool last = grp == groups - 1;
+            const bool has_next_pass = p + G < a.passes;
+            if (last && has_next_pass) row_offsets(p + G, wo);
+#pragma unroll
+            for (int u = 0; u < DEPTH; ++u) {
+                process_step(i, wb[u]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (!last) w_issue(u, step_at(i + DEPTH));
+                else if (has_next_pass) w_issue(u, step_at(u));
+                __builtin_amdgcn_sched_barrier(0);
+                ++i;
+            }
+        }
+        if (i < a.steps) {
+            // Leftover steps, not pipelined.  A chunk index past the end of the row is clamped:
+            // the bytes loaded are valid finite weights and the matching H entries are zero.
+            unsigned wr[RB][kRowsPerLane];
+            row_offsets(p, wr);
+            for (; i < a.steps; ++i) {
+                const int c = min(i * kStep16 + lk, a.d8 - 1) - lk;
+                u32x4 w[RB][kRowsPerLane];
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                    for (int r = 0; r < kRowsPerLane; ++r) w[rb][r] = load_w(Wb, wr[rb][r] + (unsigned)c * 16u);
+                process_step(i, w);
             }
         }
 
         // ---- consume the pass, one tile of 16 H rows at a time ----
-#pragma unroll
+        // (fully unrolled whatever its size: a rolled loop would index the accumulators
+        // dynamically and push them to scratch memory)
+#pragma clang loop unroll(full)
         for (int mt = 0; mt < MT16; ++mt) {
+            __syncthreads();   // z_stage is free (and, the first time, the last H chunk is done with)
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
-                float *dst = z_stage + j * (ZR + kZPad) + (wave * RB + rb) * 16 + 4 * g;
+                float *dst = z_stage + j * (kZR + kZPad) + (wave * RB + rb) * 16 + 4 * g;
                 *reinterpret_cast<f32x4_t *>(dst) = acc[rb][mt];
             }
             __syncthreads();
             if (a.sink == (int)Sink::kLogits) {
-                for (int i = tid; i < 16 * ZR; i += kMfmaThreads) {
-                    const int ml = i / ZR, r = i - ml * ZR;
+                for (int e = tid; e < 16 * kZR; e += NT) {
+                    const int ml = e / kZR, r = e - ml * kZR;
                     const int m = mt * 16 + ml;
                     if (m < a.M && r < n_valid)
-                        a.z_out[(size_t)m * a.z_ld + pass_row0 + r] = z_stage[ml * (ZR + kZPad) + r];
+                        a.z_out[(size_t)m * a.z_ld + pass_row0 + r] = z_stage[ml * (kZR + kZPad) + r];
                 }
             } else if (a.sink != (int)Sink::kStreamOnly) {
                 const int m_end = min(a.M, mt * 16 + 16);
                 auto row_of = [&](int m) {
-                    return FoldRow{z_stage + (m - mt * 16) * (ZR + kZPad), run_ms + 2 * m,
+                    return FoldRow{z_stage + (m - mt * 16) * (kZR + kZPad), run_ms + 2 * m,
                                    run_val + m * a.k, run_id + m * a.k};
                 };
                 if (p == (int)blockIdx.x)
-                    block_fold_all<ZR, false>(mt * 16 + wave, kMfmaWaves, m_end, row_of, 1, 0, ids_lds,
-                                              n_valid, a.k, &s_select[wave]);
+                    block_fold_all<kZR, false>(mt * 16 + wave, WAVES, m_end, row_of, 1, 0, ids_lds, n_valid,
+                                               a.k, &s_select[wave]);
                 else
-                    block_fold_all<ZR, true>(mt * 16 + wave, kMfmaWaves, m_end, row_of, 1, 0, ids_lds,
-                                             n_valid, a.k, &s_select[wave]);
+                    block_fold_all<kZR, true>(mt * 16 + wave, WAVES, m_end, row_of, 1, 0, ids_lds, n_valid,
+                                              a.k, &s_select[wave]);
             }
-            __syncthreads();
         }
     }
 
     if (a.sink == (int)Sink::kLogits || a.sink == (int)Sink::kStreamOnly) return;
 
-    const int gidx = blockIdx.x, G = gridDim.x;
+    __syncthreads();
+    const int gidx = blockIdx.x;
     const Partials part = a.part;   // a local copy keeps the argument block itself in registers
-    for (int m = wave; m < a.M; m += kMfmaWaves) {
+    for (int m = wave; m < a.M; m += WAVES) {
         if (lane < a.k) {
             publish(part.val + part_index(m * a.k + lane, gidx), run_val[m * a.k + lane]);
             publish(part.id + part_index(m * a.k + lane, gidx), run_id[m * a.k + lane]);
@@ -236,19 +315,29 @@ __global__ __launch_bounds__(kMfmaThreads) void mfma_kernel(MfmaArgs a) {
     const int R = merger_count(G, a.M);
     const int r = arrive_and_wait(ar, G, R, &s_slot);
     if (r < 0) return;
-    final_merge_all(part, G, r + R * wave, R * kMfmaWaves, a.M, a.k, a.token_ids, a.logp, &s_select[wave]);
+    final_merge_all(part, G, r + R * wave, R * WAVES, a.M, a.k, a.token_ids, a.logp, &s_select[wave]);
     merger_done(ar, R);
 }
 
 constexpr int kLdsBudget = 160 * 1024;
 constexpr int kStaticLdsReserve = 8 * 1024;   // room for the kernel's static LDS (selection scratch)
-constexpr int kRB = 2;
-constexpr int kPD = 3;
-constexpr int kZR = kMfmaWaves * kRB * 16;
 
-template <int MT16>
-fr_status launch_one(const MfmaArgs &a, int grid, int lds, hipStream_t s) {
-    auto kern = mfma_kernel<MT16, kRB, kPD>;
+struct Build {
+    int mt16, hch;
+};
+// m tiles -> H chunk length (in half-steps of 64 elements) of the build that serves them
+constexpr Build kBuilds[] = {{1, 4}, {2, 4}, {4, 4}, {8, 2}, {12, 1}, {16, 1}};
+
+const Build *build_for(int M) {
+    const int t = (M + 15) / 16;
+    for (const Build &b : kBuilds)
+        if (t <= b.mt16) return &b;
+    return nullptr;
+}
+
+template <int MT16, int RB, int WAVES, int DEPTH, int HCH>
+fr_status launch_one(const WideArgs &a, int grid, int lds, hipStream_t s) {
+    auto kern = wide_kernel<MT16, RB, WAVES, DEPTH, HCH>;
     static bool attr_done = false;
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -259,37 +348,30 @@ fr_status launch_one(const MfmaArgs &a, int grid, int lds, hipStream_t s) {
         }
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kMfmaThreads), lds, s, a);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(WAVES * kWave), lds, s, a);
     return hip_status(hipGetLastError());
-}
-
-int mt16_bucket(int M) {
-    const int t = (M + 15) / 16;
-    for (int b : {1, 2, 4, 8, 12, 16})
-        if (t <= b) return b;
-    return -1;
 }
 
 }  // namespace
 
-// Largest slab of H rows (multiple of 16, <= 256) whose state fits LDS for this k.
+// Largest slab of H rows (multiple of 16, <= 256) whose per-row state fits LDS for this k.
 int mfma_max_rows(int k) {
     int best = 0;
-    for (int mt : {1, 2, 4, 8, 12, 16})
-        if (MfmaLds(mt, kZR, k).total <= kLdsBudget - kStaticLdsReserve) best = mt * 16;
+    for (const Build &b : kBuilds)
+        if (WideLds(b.mt16, b.hch, k).total <= kLdsBudget - kStaticLdsReserve) best = b.mt16 * 16;
     return best;
 }
 
 fr_status launch_mfma(const HeadProblem &p, Sink sink, const fr_tuning *t, hipStream_t s,
                       int *grid_used) {
-    const int MT16 = mt16_bucket(p.M);
-    if (MT16 < 0) return FR_ERR_UNSUPPORTED;
-    const int lds = MfmaLds(MT16, kZR, p.k).total;
+    const Build *b = build_for(p.M);
+    if (!b) return FR_ERR_UNSUPPORTED;
+    const int lds = WideLds(b->mt16, b->hch, p.k).total;
     if (lds > kLdsBudget - kStaticLdsReserve) return FR_ERR_UNSUPPORTED;
     const int cus = device_cu_count();
     if (cus <= 0) return FR_ERR_HIP;
 
-    MfmaArgs a{};
+    WideArgs a{};
     a.H = static_cast<const u32x4 *>(p.H);
     a.W = static_cast<const u32x4 *>(p.W);
     a.idx_map = p.idx_map;
@@ -297,7 +379,7 @@ fr_status launch_mfma(const HeadProblem &p, Sink sink, const fr_tuning *t, hipSt
     a.d8 = p.d / 8;
     a.V_rows = p.V_rows;
     a.k = p.k;
-    a.chunks = (a.d8 + kChunk16 - 1) / kChunk16;
+    a.steps = (a.d8 + kStep16 - 1) / kStep16;
     a.passes = (p.V_rows + kZR - 1) / kZR;
     a.sink = (int)sink;
     a.part.ms = p.ws.part_ms;
@@ -309,24 +391,19 @@ fr_status launch_mfma(const HeadProblem &p, Sink sink, const fr_tuning *t, hipSt
     a.z_out = p.z_out;
     a.z_ld = p.z_ld;
 
-    // workgroups per compute unit that the LDS footprint allows
-    int per_cu = kLdsBudget / (lds + 512);
-    if (per_cu < 1) per_cu = 1;
-    if (per_cu > 2) per_cu = 2;
-    int grid = cus * per_cu;
-    if (grid > a.passes) grid = a.passes;
+    int grid = cus < a.passes ? cus : a.passes;   // one persistent workgroup per compute unit
     if (t && t->grid > 0) grid = t->grid < a.passes ? t->grid : a.passes;
     if (grid > kGridMax) grid = kGridMax;
     if (grid_used) *grid_used = grid;
 
     fr_status st = FR_ERR_UNSUPPORTED;
-    switch (MT16) {
-        case 1: st = launch_one<1>(a, grid, lds, s); break;
-        case 2: st = launch_one<2>(a, grid, lds, s); break;
-        case 4: st = launch_one<4>(a, grid, lds, s); break;
-        case 8: st = launch_one<8>(a, grid, lds, s); break;
-        case 12: st = launch_one<12>(a, grid, lds, s); break;
-        case 16: st = launch_one<16>(a, grid, lds, s); break;
+    switch (b->mt16) {
+        case 1: st = launch_one<1, 1, 8, 4, 4>(a, grid, lds, s); break;
+        case 2: st = launch_one<2, 1, 8, 4, 4>(a, grid, lds, s); break;
+        case 4: st = launch_one<4, 1, 8, 4, 4>(a, grid, lds, s); break;
+        case 8: st = launch_one<8, 2, 4, 2, 2>(a, grid, lds, s); break;
+        case 12: st = launch_one<12, 2, 4, 2, 1>(a, grid, lds, s); break;
+        case 16: st = launch_one<16, 2, 4, 2, 1>(a, grid, lds, s); break;
     }
     if (st != FR_OK) return st;
     if (sink == Sink::kPartialsOnly) return launch_merge(p, grid, s);
