@@ -153,7 +153,30 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     constexpr unsigned kStepBytes = kStep16 * 16;
     constexpr unsigned kGroupBytes = DEPTH * kStepBytes;
 
-    // W is requested before anything else so that HBM is busy while H is staged
+    // Start of the stream.  Loads return in issue order, so the (small, L2-resident) H is
+    // requested first and W right behind it: H can then be written to LDS while the first
+    // W stages are still on their way, and the first products start as soon as W arrives.
+    // Requested the other way round, H would queue behind 16 W loads per lane.
+    constexpr int NT = WAVES * kWave;
+    constexpr int kHPre = 12;   // 16-byte pieces of H per thread held in registers meanwhile
+    const int h_total = hrows * hpitch;
+    u32x4 hpre[kHPre];
+    {
+        // piece i = tid + u * NT sits at (row m, chunk c) of the padded H; advanced without
+        // dividing by the run-time pitch
+        int m = tid / hpitch, c = tid - m * hpitch;
+#pragma unroll
+        for (int u = 0; u < kHPre; ++u) {
+            const bool real = m < a.M && m < hrows && c < a.d8;
+            const u32x4 v = a.H[real ? (size_t)m * a.d8 + c : 0];   // unconditional: loads stay back to back
+            hpre[u] = real ? v : zero_u32x4();
+            c += NT;
+            while (c >= hpitch) {
+                c -= hpitch;
+                ++m;
+            }
+        }
+    }
     u32x4 wb[DEPTH][kRowsPerLane];
     unsigned wo[kRowsPerLane];
     const int first_pass = (int)blockIdx.x;
@@ -169,7 +192,10 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
 
     // stage H (zero padded to whole steps, and to MT rows where the tiles need it) and
     // reset the running state
-    for (int i = tid; i < hrows * hpitch; i += WAVES * kWave) {
+#pragma unroll
+    for (int u = 0; u < kHPre; ++u)
+        if (tid + u * NT < h_total) H_lds[tid + u * NT] = hpre[u];
+    for (int i = tid + kHPre * NT; i < h_total; i += NT) {
         const int m = i / hpitch, c = i - m * hpitch;
         u32x4 v = zero_u32x4();
         if (m < a.M && c < a.d8) v = a.H[(size_t)m * a.d8 + c];
