@@ -44,37 +44,59 @@ __device__ __forceinline__ T observe(const T *p) {
 // Blocks the wavefront until its outstanding stores have been acknowledged.
 __device__ __forceinline__ void wait_stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-// Arrival words at the start of the workspace (all zero between calls).
-struct Arrival {
-    unsigned *ticket;   // workgroups that have published their partials
-    unsigned *done;     // merging workgroups that have finished
-    unsigned *error;    // sticky: set to 1 if a bounded wait ever ran out
-};
+// Arrival words at the start of the workspace.  Two arrival counters take turns from call
+// to call (`parity` says whose turn it is), each on a cache line of its own.
 constexpr int kMaxMergers = 32;          // far fewer than the workgroups resident at once
-constexpr unsigned kSpinLimit = 1u << 22;   // polls of ~0.5 us each before giving up
+constexpr unsigned kSpinLimit = 1u << 22;   // polls of ~0.2 us each before giving up
+struct Arrival {
+    unsigned *parity;
+    unsigned *error;    // sticky: set to 1 if a bounded wait ever ran out
+    unsigned *count;    // count[0] and count[32]
+    __device__ explicit Arrival(unsigned *header) : parity(header), error(header + 1), count(header + 32) {}
+    // Which counter this call uses; read by every workgroup when it starts.
+    __device__ unsigned turn() const { return __hip_atomic_load(parity, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & 1u; }
+};
 
 /*
- * The merge of the partials is shared by the last R = min(G, M, kMaxMergers) workgroups
- * to arrive: workgroup number r of those merges rows r, r + R, ... of H.  One workgroup
- * merging every row would run M single-wavefront jobs on the four SIMDs of one compute
- * unit; spread over R compute units the jobs run side by side.
+ * The merge of the partials is shared by the first R = min(G, M, kMaxMergers) workgroups
+ * to arrive: number r of those merges rows r, r + R, ... of H once all G have arrived.
+ * The early finishers have nothing else left to do, and the last workgroup to arrive (the
+ * one everybody waits for) only posts its arrival: the mergers see it one memory hop later.
  *
- * Every thread of a workgroup calls this after publishing its partials.  Returns -1 in
- * workgroups that are not among the last R (they are finished), else r, after all G
- * workgroups have arrived.  The wait is on workgroups that are already running and need
- * nothing from the waiters, and at most kMaxMergers workgroups ever wait, so it cannot
- * starve a workgroup that has not been scheduled yet; it is bounded all the same.
+ * An arriving workgroup draws its arrival number from this call's counter; the mergers
+ * poll that counter, several polls in flight, until it shows G.  The workgroup that draws
+ * the last number clears the OTHER counter (last used by the previous call, which is long
+ * over) and hands the turn to it, so the next call starts from zero and no merger has to
+ * write, or wait for, anything once its rows are out.
+ *
+ * Every thread of a workgroup calls this after publishing its partials; `turn` is the
+ * value read when the workgroup started.  Returns -1 in workgroups that do not merge
+ * (they are finished), else r, after all G workgroups have arrived.  At most kMaxMergers
+ * workgroups ever wait, the workgroups they wait for need nothing from them, and a
+ * waiting workgroup occupies one compute unit of many, so the wait cannot starve a
+ * workgroup that has not been scheduled yet; it is bounded all the same.
  */
-__device__ __forceinline__ int arrive_and_wait(const Arrival &ar, int G, int R, int *s_slot) {
+__device__ __forceinline__ int arrive_and_wait(const Arrival &ar, unsigned turn, int G, int R, int *s_slot) {
     wait_stores_done();
     __syncthreads();
     if (threadIdx.x == 0) {
-        const unsigned a = __hip_atomic_fetch_add(ar.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        int r = (int)a - (G - R);
+        unsigned *mine = ar.count + 32 * turn;
+        const unsigned a = __hip_atomic_fetch_add(mine, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (a == (unsigned)(G - 1)) {
+            __hip_atomic_store(ar.count + 32 * (turn ^ 1u), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(ar.parity, turn ^ 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        const int r = a < (unsigned)R ? (int)a : -1;
         if (r >= 0) {
+            auto poll = [mine]() { return __hip_atomic_load(mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
+            unsigned q0 = poll(), q1 = poll(), q2 = poll(), q3 = poll();   // oldest first
             unsigned polls = 0;
-            while (__hip_atomic_load(ar.ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < (unsigned)G) {
-                __builtin_amdgcn_s_sleep(4);
+            while (q0 < (unsigned)G) {
+                q0 = q1;
+                q1 = q2;
+                q2 = q3;
+                q3 = poll();
+                __builtin_amdgcn_s_sleep(1);
                 if (++polls > kSpinLimit) {
                     __hip_atomic_store(ar.error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     break;
@@ -85,19 +107,6 @@ __device__ __forceinline__ int arrive_and_wait(const Arrival &ar, int G, int R, 
     }
     __syncthreads();
     return *s_slot;
-}
-
-// Called by every thread of a merging workgroup when its rows are written; the last
-// merger to finish clears the arrival words for the next call.
-__device__ __forceinline__ void merger_done(const Arrival &ar, int R) {
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const unsigned d = __hip_atomic_fetch_add(ar.done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (d == (unsigned)(R - 1)) {
-            __hip_atomic_store(ar.done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(ar.ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
 }
 
 __device__ __forceinline__ int merger_count(int G, int M) {
@@ -226,12 +235,231 @@ __device__ __forceinline__ void block_fold_all(int first, int stride, int M, Row
     }
 }
 
+
+// ---------------------------------------------------------------------------------------
+// Fast paths for k <= kSmallKMax (16).  Both rest on the same bound: split the candidates
+// into 16 groups; the k-th largest of the 16 group maxima is a lower bound of the k-th best
+// candidate overall (k different groups hold a candidate at least that good), so only the
+// candidates at or above it, k plus a few in expectation, need to be ranked.  The 16 group
+// maxima sit in the 16 lanes of a DPP row, where the k-th largest takes 15 row rotations.
+// ---------------------------------------------------------------------------------------
+
+typedef float fvec4 __attribute__((ext_vector_type(4)));
+typedef float fvec2 __attribute__((ext_vector_type(2)));
+typedef int ivec4 __attribute__((ext_vector_type(4)));
+typedef int ivec2 __attribute__((ext_vector_type(2)));
+typedef unsigned long long u64x2 __attribute__((ext_vector_type(2)));
+
+// C consecutive 4-byte words of LDS, as one access.
+template <int C, typename T, typename V4, typename V2>
+__device__ __forceinline__ void lds_words(const T *p, T (&out)[C]) {
+    static_assert(C == 1 || C == 2 || C == 4, "1, 2 or 4 words per lane");
+    if constexpr (C == 4) {
+        const V4 v = *reinterpret_cast<const V4 *>(p);
+        out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+    } else if constexpr (C == 2) {
+        const V2 v = *reinterpret_cast<const V2 *>(p);
+        out[0] = v.x; out[1] = v.y;
+    } else {
+        out[0] = *p;
+    }
+}
+
+// Where a fold puts its results: the workgroup's running state in LDS, or, on the
+// workgroup's last pass, straight into the workspace (slot g of the partials).
+struct FoldSink {
+    bool to_global;
+    Partials part;
+    int g;
+    float *run_ms;
+    float *run_val;
+    int *run_id;
+    __device__ __forceinline__ void entry(int m, int k, int slot, float v, int id) const {
+        if (to_global) {
+            publish(part.val + part_index(m * k + slot, g), v);
+            publish(part.id + part_index(m * k + slot, g), id);
+        } else {
+            run_val[m * k + slot] = v;
+            run_id[m * k + slot] = id;
+        }
+    }
+    __device__ __forceinline__ void stats(int m, float mx, float S) const {
+        if (to_global) {
+            publish(part.ms + part_index(m * 2, g), mx);
+            publish(part.ms + part_index(m * 2 + 1, g), S);
+        } else {
+            run_ms[2 * m] = mx;
+            run_ms[2 * m + 1] = S;
+        }
+    }
+};
+
 /*
- * One wavefront merges the G partial results of NS rows of H and writes their outputs.
- * Every partial list is sorted, so the k best overall lie in the k lists with the best
- * heads, and list number i (by head) can contribute at most k - i entries: the search
- * space shrinks from G*k to k(k+1)/2 candidates.  HPL = ceil(G / 64) heads per lane.
+ * One wavefront folds one pass of logits of TWO rows of H at once, one per half of the
+ * wavefront: lane (h, l32) works on row `m` (the same for the 32 lanes of a half;
+ * `active` false if that row does not exist) and holds C = ZR_MAX / 32 consecutive local
+ * vocabulary rows, plus entry l32 of the row's running list when WITH_RUN.  A group is
+ * the pair of lanes (l32, l32 ^ 16).
+ *   z_lds   logits of the pass, row m at z_lds + m * ZR (+ q * z_slice_stride for slice q
+ *           of a split d); the logit is the sum of the slices in slice order
+ * Returns false, having written nothing, when more than 32 candidates of a row survive
+ * the bound (heavily tied values, or fewer than k populated groups): the caller then
+ * takes the general path for both rows.
  */
+template <int ZR_MAX, bool WITH_RUN>
+__device__ __forceinline__ bool fold_pair_fast(const float *z_lds, int ZR, int KS, int z_slice_stride,
+                                               const int *ids_pass, int n_valid, int k, int m, bool active,
+                                               const FoldSink &out, SelectScratch *sc) {
+    constexpr int C = ZR_MAX / 32;
+    constexpr int CPL = C + (WITH_RUN ? 1 : 0);
+    const int lane = lane_id(), h = lane >> 5, l32 = lane & 31;
+    const int mm = active ? m : 0;
+
+    float z[C];
+#pragma unroll
+    for (int c = 0; c < C; ++c) z[c] = 0.0f;
+    const float *zp = z_lds + mm * ZR + l32 * C;
+    for (int q = 0; q < KS; ++q) {
+        float t[C];
+        lds_words<C, float, fvec4, fvec2>(zp + q * z_slice_stride, t);
+#pragma unroll
+        for (int c = 0; c < C; ++c) z[c] += t[c];
+    }
+    int id[C];
+    lds_words<C, int, ivec4, ivec2>(ids_pass + l32 * C, id);
+    const int kk = l32 < k ? l32 : k - 1;
+    float old_mx = kNegInf, old_S = 0.0f, run_v = kNegInf;
+    int run_i = INT_MAX;
+    if (WITH_RUN) {
+        old_mx = out.run_ms[2 * mm];
+        old_S = out.run_ms[2 * mm + 1];
+        run_v = out.run_val[mm * k + kk];
+        run_i = out.run_id[mm * k + kk];
+        if (!(active && l32 < k)) run_i = INT_MAX;
+    }
+
+    // online softmax statistics of the row (Eq. 4's normaliser, accumulated per pass)
+    float v[C];
+    bool ok[C];
+    float lmax = kNegInf;
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+        ok[c] = active && (l32 * C + c < n_valid);
+        v[c] = ok[c] ? z[c] : kNegInf;
+        lmax = fmaxf(lmax, v[c]);
+    }
+    const float mx = fmaxf(old_mx, row16_max_f32(fmaxf(lmax, swap16_f32(lmax))));
+    float part = 0.0f;
+#pragma unroll
+    for (int c = 0; c < C; ++c) part += exp_diff(v[c], mx);
+    part += swap16_f32(part);
+    const float S = old_S * exp_diff(old_mx, mx) + row16_sum_all(part);
+
+    // candidates as keys, and the bound
+    unsigned hi[CPL], lo[CPL];
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+        hi[c] = ok[c] ? key_hi_of(v[c]) : 0u;
+        lo[c] = ~(unsigned)id[c];
+    }
+    if (WITH_RUN) {
+        hi[CPL - 1] = run_i != INT_MAX ? key_hi_of(run_v) : 0u;
+        lo[CPL - 1] = ~(unsigned)run_i;
+    }
+    unsigned lm = hi[0];
+#pragma unroll
+    for (int c = 1; c < CPL; ++c) lm = max(lm, hi[c]);
+    const unsigned L = row16_kth_largest_u32(max(lm, swap16_u32(lm)), k);
+
+    // survivors of each half, packed into its 32 scratch slots
+    sc->key[lane] = 0ull;
+    int n0 = 0, n1 = 0;
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+        const bool sv = hi[c] != 0u && hi[c] >= L;
+        const unsigned long long mask = __ballot(sv);
+        const int c_lo = __popc((unsigned)mask), c_hi = __popc((unsigned)(mask >> 32));
+        const int before = (int)__builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32),
+                                                          __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u));
+        const int pos = h ? before - c_lo + n1 : before + n0;
+        if (sv && pos < 32) sc->key[h * 32 + pos] = make_key(hi[c], lo[c]);
+        n0 += c_lo;
+        n1 += c_hi;
+    }
+    if (n0 > 32 || n1 > 32) return false;
+
+    // rank = number of better survivors of the same row (the unused slots hold zero keys)
+    const unsigned long long mine = sc->key[lane];
+    const u64x2 *kp = reinterpret_cast<const u64x2 *>(sc->key + h * 32);
+    const int nmax = n0 > n1 ? n0 : n1;
+    int rank = 0;
+#pragma unroll 4
+    for (int j = 0; j < nmax; j += 2) {
+        const u64x2 two = kp[j >> 1];
+        rank += two.x > mine;
+        rank += two.y > mine;
+    }
+    if (active) {
+        const int n_h = h ? n1 : n0;
+        if (mine != 0ull && rank < k)
+            out.entry(m, k, rank, value_of_key_hi((unsigned)(mine >> 32)), (int)~(unsigned)mine);
+        if (l32 >= n_h && l32 < k) out.entry(m, k, l32, kNegInf, INT_MAX);   // fewer candidates than k
+        if (l32 == 0) out.stats(m, mx, S);
+    }
+    return true;
+}
+
+// General fold of one row by one whole wavefront, kept out of line: any k, any number of
+// tied values.  On the workgroup's last pass the row is also published.
+template <int ZR, bool WITH_RUN>
+__device__ __noinline__ void fold_row_general(FoldRow row, int KS, int z_slice_stride, const int *ids_pass,
+                                              int n_valid, int k, SelectScratch *sc, bool to_global,
+                                              Partials part, int m, int g) {
+    const FoldRow rows[1] = {row};
+    block_fold_rows<ZR, 1, WITH_RUN>(rows, KS, z_slice_stride, ids_pass, n_valid, k, sc);
+    if (to_global) {
+        const int lane = lane_id();
+        if (lane < k) {
+            publish(part.val + part_index(m * k + lane, g), row.run_val[lane]);
+            publish(part.id + part_index(m * k + lane, g), row.run_id[lane]);
+        }
+        if (lane < 2) publish(part.ms + part_index(m * 2 + lane, g), row.run_ms[lane]);
+    }
+}
+
+/*
+ * Folds one pass into the running state of all M rows of H; on the workgroup's last pass
+ * (`to_global`) the result goes straight to slot g of the partials instead.  Wavefront w
+ * of `waves` takes rows w and w + waves (then + 2 * waves, ...), two at a time in its two
+ * halves while k <= 16.
+ */
+template <int ZR_MAX, bool WITH_RUN, typename RowOf>
+__device__ __forceinline__ void fold_pass(const float *z_lds, int ZR, int KS, int z_slice_stride,
+                                          const int *ids_pass, int n_valid, int k, int M, int wave, int waves,
+                                          RowOf row_of, float *run_ms, float *run_val, int *run_id,
+                                          bool to_global, const Partials &part, int g, SelectScratch *sc) {
+    if (k <= kSmallKMax) {
+        const FoldSink out{to_global, part, g, run_ms, run_val, run_id};
+        for (int mb = 0; mb < M; mb += 2 * waves) {
+            const int m_lo = mb + wave, m_hi = mb + wave + waves;
+            if (m_lo >= M) break;
+            const int m = (lane_id() >> 5) ? m_hi : m_lo;
+            if (fold_pair_fast<ZR_MAX, WITH_RUN>(z_lds, ZR, KS, z_slice_stride, ids_pass, n_valid, k, m, m < M,
+                                                 out, sc))
+                continue;
+            fold_row_general<ZR_MAX, WITH_RUN>(row_of(m_lo), KS, z_slice_stride, ids_pass, n_valid, k, sc,
+                                               to_global, part, m_lo, g);
+            if (m_hi < M)
+                fold_row_general<ZR_MAX, WITH_RUN>(row_of(m_hi), KS, z_slice_stride, ids_pass, n_valid, k, sc,
+                                                   to_global, part, m_hi, g);
+        }
+    } else {
+        for (int m = wave; m < M; m += waves)
+            fold_row_general<ZR_MAX, WITH_RUN>(row_of(m), KS, z_slice_stride, ids_pass, n_valid, k, sc,
+                                               to_global, part, m, g);
+    }
+}
+
 #ifdef FRSPEC_MERGE_TRACE
 #define FRSPEC_MERGE_STAMP(i) \
     do { if (lane_id() == 0) FRSPEC_MERGE_TRACE[i] = (long long)__builtin_readcyclecounter(); } while (0)
@@ -465,6 +693,144 @@ __device__ __forceinline__ void final_merge_all(const Partials &P, int G, int fi
     if (m < M) {
         const int ms[1] = {m};
         final_merge_dispatch<1>(P, G, ms, k, token_ids, logp, sc);
+    }
+}
+
+
+// Scratch of the fast merge, one per workgroup.
+struct alignas(16) MergeScratch {
+    unsigned long long key[kWave];
+    unsigned count;
+    float logZ;
+};
+
+// The general merge of a set of rows by one wavefront, kept out of line.
+__device__ __noinline__ void final_merge_general(Partials P, int G, int first, int stride, int M, int k,
+                                                 int *token_ids, float *logp, SelectScratch *sc) {
+    final_merge_all(P, G, first, stride, M, k, token_ids, logp, sc);
+}
+
+/*
+ * A workgroup merges the G <= 256 partial results of rows first, first + stride, ... of H,
+ * k <= 16.  One trip to memory per row.  Four wavefronts (one per SIMD; the others only
+ * keep the barriers company) fetch the G list heads, for the bound, and entry t of all G
+ * lists for the list positions t = wave, wave + 4, ...; the last of the four also fetches
+ * the softmax statistics.  The groups of the bound are the 16 sets of heads
+ * {g : g mod 16 = j}.  Each wavefront keeps those of its entries that reach the bound
+ * (k plus a few survive, out of G * k: most registers hold none, and those are skipped),
+ * the survivors meet in LDS, and the first wavefront ranks them and writes the outputs.
+ */
+__device__ __forceinline__ void merge_rows_fast(const Partials &P, int G, int first, int stride, int M, int k,
+                                                int *token_ids, float *logp, MergeScratch *ms,
+                                                SelectScratch *sc) {
+    constexpr int HPL = 4;                      // G <= 256
+    constexpr int NW = 4;                       // fetching wavefronts
+    constexpr int TPW = kSmallKMax / NW;        // list positions per fetching wavefront
+    const int lane = lane_id();
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x / kWave);
+    for (int m = first; m < M; m += stride) {
+        if (wave == 0) {
+            ms->key[lane] = 0ull;
+            if (lane == 0) ms->count = 0u;
+        }
+        __syncthreads();
+        if (wave < NW) {
+            // ---- every load of the row, unconditional from clamped addresses
+            float hv[HPL], ev[TPW][HPL], mxs[HPL], Ss[HPL];
+            int eid[TPW][HPL];
+#pragma unroll
+            for (int q = 0; q < HPL; ++q) {
+                const int g = lane + kWave * q, gs = g < G ? g : G - 1;
+                hv[q] = observe(P.val + part_index(m * k, gs));
+#pragma unroll
+                for (int j = 0; j < TPW; ++j) {
+                    const int t = wave + j * NW, ts = t < k ? t : 0;
+                    ev[j][q] = observe(P.val + part_index(m * k + ts, gs));
+                    eid[j][q] = observe(P.id + part_index(m * k + ts, gs));
+                }
+            }
+            if (wave == NW - 1) {
+#pragma unroll
+                for (int q = 0; q < HPL; ++q) {
+                    const int g = lane + kWave * q, gs = g < G ? g : G - 1;
+                    mxs[q] = observe(P.ms + part_index(m * 2, gs));
+                    Ss[q] = observe(P.ms + part_index(m * 2 + 1, gs));
+                }
+            }
+
+            // ---- the bound (every fetching wavefront computes the same one).  Maxima are
+            // taken as floats (a NaN head just does not take part) and ordered as keys.
+            float lmax = kNegInf;
+#pragma unroll
+            for (int q = 0; q < HPL; ++q) lmax = fmaxf(lmax, lane + kWave * q < G ? hv[q] : kNegInf);
+            unsigned gm = key_hi_of(lmax);
+            gm = max(gm, swap16_u32(gm));
+            gm = max(gm, swap32_u32(gm));
+            const float bound = value_of_key_hi(row16_kth_largest_u32(gm, k));
+
+            // ---- survivors among this wavefront's entries: not below the bound (a NaN
+            // is not below anything, and ranks first like in the key order)
+#pragma unroll
+            for (int j = 0; j < TPW; ++j)
+#pragma unroll
+                for (int q = 0; q < HPL; ++q) {
+                    const bool real = (wave + j * NW < k) && (lane + kWave * q < G) && eid[j][q] != INT_MAX;
+                    const bool sv = real && !(ev[j][q] < bound);
+                    const unsigned long long mk = __ballot(sv);
+                    if (mk != 0ull) {
+                        unsigned base = 0u;
+                        if (lane == 0) base = atomicAdd(&ms->count, (unsigned)__popcll(mk));
+                        const int pos = __builtin_amdgcn_readfirstlane((int)base) +
+                                        (int)__builtin_amdgcn_mbcnt_hi((unsigned)(mk >> 32),
+                                                                       __builtin_amdgcn_mbcnt_lo((unsigned)mk, 0u));
+                        if (sv && pos < kWave) ms->key[pos] = make_key(key_hi_of(ev[j][q]), ~(unsigned)eid[j][q]);
+                    }
+                }
+            if (wave == NW - 1) {
+                // log Z = mx + log sum_g S_g exp(mx_g - mx)
+                float lmx = kNegInf;
+#pragma unroll
+                for (int q = 0; q < HPL; ++q) {
+                    const bool ok = lane + kWave * q < G;
+                    mxs[q] = ok ? mxs[q] : kNegInf;
+                    Ss[q] = ok ? Ss[q] : 0.0f;
+                    lmx = fmaxf(lmx, mxs[q]);
+                }
+                const float mx = wave_max_f32(lmx);
+                float part = 0.0f;
+#pragma unroll
+                for (int q = 0; q < HPL; ++q) part += Ss[q] * exp_diff(mxs[q], mx);
+                const float logZ = mx + __logf(wave_sum_f32(part));
+                if (lane == 0) ms->logZ = logZ;
+            }
+        }
+        __syncthreads();
+
+        if (wave == 0) {
+            const int n = __builtin_amdgcn_readfirstlane((int)ms->count);
+            if (n <= kWave) {
+                const unsigned long long mine = ms->key[lane];
+                const float logZ = ms->logZ;
+                const u64x2 *kp = reinterpret_cast<const u64x2 *>(ms->key);
+                int rank = 0;
+#pragma unroll 4
+                for (int j = 0; j < n; j += 2) {
+                    const u64x2 two = kp[j >> 1];
+                    rank += two.x > mine;
+                    rank += two.y > mine;
+                }
+                if (mine != 0ull && rank < k) {
+                    token_ids[(size_t)m * k + rank] = (int)~(unsigned)mine;
+                    logp[(size_t)m * k + rank] = value_of_key_hi((unsigned)(mine >> 32)) - logZ;
+                }
+                if (lane >= n && lane < k) {   // fewer candidates than k in the whole subset
+                    token_ids[(size_t)m * k + lane] = INT_MAX;
+                    logp[(size_t)m * k + lane] = kNegInf;
+                }
+            } else {
+                final_merge_general(P, G, m, M, M, k, token_ids, logp, sc);   // this row only
+            }
+        }
     }
 }
 

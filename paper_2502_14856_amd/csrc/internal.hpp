@@ -37,7 +37,7 @@ struct HeadProblem {
     WorkspaceView ws;
 };
 
-constexpr size_t kWorkspaceHeaderBytes = 256;
+constexpr size_t kWorkspaceHeaderBytes = 512;
 constexpr int kWorkspaceGridMax = 512;   // partial slots reserved per row of H
 constexpr int kMatrixPathMaxM = 256;     // rows of H per matrix-core launch
 constexpr int kSkinnyMaxM = 16;          // rows of H the vector-ALU kernel covers

@@ -96,6 +96,9 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
     const int lk = lane & 15, rs = lane >> 4;   // load layout: 16-byte chunk, row slot
     const int j = lk, g = rs;                   // operand layout: row / column, k group
     const int G = gridDim.x;
+    // which arrival counter this call uses: asked for now, needed at the very end
+    const Arrival ar(a.ticket);
+    const unsigned turn = a.sink == (int)Sink::kFusedTopk ? ar.turn() : 0u;
 
     for (int i = tid; i < Mp * a.k; i += NT) {
         run_val[i] = kNegInf;
@@ -311,12 +314,10 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
     }
     if (a.sink == (int)Sink::kPartialsOnly) return;
 
-    const Arrival ar{a.ticket, a.ticket + 1, a.ticket + 2};
     const int R = merger_count(G, a.M);
-    const int r = arrive_and_wait(ar, G, R, &s_slot);
+    const int r = arrive_and_wait(ar, (unsigned)__builtin_amdgcn_readfirstlane((int)turn), G, R, &s_slot);
     if (r < 0) return;
     final_merge_all(part, G, r + R * wave, R * WAVES, a.M, a.k, a.token_ids, a.logp, &s_select[wave]);
-    merger_done(ar, R);
 }
 
 constexpr int kLdsBudget = 160 * 1024;

@@ -104,6 +104,8 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     int *run_id = reinterpret_cast<int *>(base + L.id_off);
     __shared__ int s_slot;
     __shared__ SelectScratch s_select[WAVES];
+    __shared__ MergeScratch s_merge;
+    const Partials part = a.part;   // a local copy keeps the argument block itself in registers
 
     constexpr int ZR_MAX = WAVES * kTileRows;
     constexpr int kStep16 = kLanesAlongD;        // 16-byte chunks per row per step
@@ -122,6 +124,9 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
         if (a.trace && tid == 0) a.trace[blockIdx.x * 8 + slot] = (long long)__builtin_amdgcn_s_memrealtime();
     };
     stamp(0);
+    // which arrival counter this call uses: asked for now, needed at the very end
+    const Arrival ar(a.ticket);
+    const unsigned turn = a.sink == (int)Sink::kFusedTopk ? ar.turn() : 0u;
 
     // Step range of this wavefront along d, split into a pipelined part (whole groups of
     // DEPTH full steps, no bounds handling at all) and leftovers (at most DEPTH - 1 steps,
@@ -190,8 +195,7 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
                 wb[u][r] = load_w(Wb, wo[r] + g_first * kGroupBytes + u * kStepBytes);
     }
 
-    // stage H (zero padded to whole steps, and to MT rows where the tiles need it) and
-    // reset the running state
+    // stage H (zero padded to whole steps, and to MT rows where the tiles need it)
 #pragma unroll
     for (int u = 0; u < kHPre; ++u)
         if (tid + u * NT < h_total) H_lds[tid + u * NT] = hpre[u];
@@ -201,14 +205,7 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
         if (m < a.M && c < a.d8) v = a.H[(size_t)m * a.d8 + c];
         H_lds[i] = v;
     }
-    for (int i = tid; i < MT * a.k; i += WAVES * kWave) {
-        run_val[i] = kNegInf;
-        run_id[i] = INT_MAX;
-    }
-    if (tid < MT) {
-        run_ms[2 * tid] = kNegInf;
-        run_ms[2 * tid + 1] = 0.0f;
-    }
+    // (the running state needs no reset: a workgroup's first pass overwrites all of it)
     __syncthreads();
     stamp(1);
 
@@ -370,37 +367,31 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
             auto row_of = [&](int m) {
                 return FoldRow{z_lds + m * ZR, run_ms + 2 * m, run_val + m * a.k, run_id + m * a.k};
             };
+            // the last pass of the workgroup publishes its result instead of keeping it
+            const bool last = p + G >= a.passes;
             if (p == first_pass)
-                block_fold_all<ZR_MAX, false>(wave, WAVES, a.M, row_of, KS, MT * ZR, ids_lds, n_valid, a.k, &s_select[wave]);
+                fold_pass<ZR_MAX, false>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, a.M, wave, WAVES, row_of,
+                                         run_ms, run_val, run_id, last, part, (int)blockIdx.x, &s_select[wave]);
             else
-                block_fold_all<ZR_MAX, true>(wave, WAVES, a.M, row_of, KS, MT * ZR, ids_lds, n_valid, a.k, &s_select[wave]);
+                fold_pass<ZR_MAX, true>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, a.M, wave, WAVES, row_of,
+                                        run_ms, run_val, run_id, last, part, (int)blockIdx.x, &s_select[wave]);
         }
-        __syncthreads();
+        if (p + G < a.passes) __syncthreads();
     }
 
     if (a.sink == (int)Sink::kLogits || a.sink == (int)Sink::kStreamOnly) return;
-
-    // ---- publish this workgroup's partials ----
-    const Partials part = a.part;   // a local copy keeps the argument block itself in registers
     stamp(3);
-    const int g = blockIdx.x;
-    for (int m = wave; m < a.M; m += WAVES) {
-        if (lane < a.k) {
-            publish(part.val + part_index(m * a.k + lane, g), run_val[m * a.k + lane]);
-            publish(part.id + part_index(m * a.k + lane, g), run_id[m * a.k + lane]);
-        }
-        if (lane < 2) publish(part.ms + part_index(m * 2 + lane, g), run_ms[2 * m + lane]);
-    }
     if (a.sink == (int)Sink::kPartialsOnly) return;
 
-    // ---- the last workgroup to arrive merges all partials (single launch) ----
-    const Arrival ar{a.ticket, a.ticket + 1, a.ticket + 2};
+    // ---- the first workgroups to arrive merge all partials (single launch) ----
     const int R = merger_count(G, a.M);
-    const int r = arrive_and_wait(ar, G, R, &s_slot);
+    const int r = arrive_and_wait(ar, (unsigned)__builtin_amdgcn_readfirstlane((int)turn), G, R, &s_slot);
     stamp(4);
     if (r < 0) return;
-    final_merge_all(part, G, r + R * wave, R * WAVES, a.M, a.k, a.token_ids, a.logp, &s_select[wave]);
-    merger_done(ar, R);
+    if (a.k <= kSmallKMax && G <= 4 * kWave)
+        merge_rows_fast(part, G, r, R, a.M, a.k, a.token_ids, a.logp, &s_merge, &s_select[0]);
+    else
+        final_merge_general(part, G, r + R * wave, R * WAVES, a.M, a.k, a.token_ids, a.logp, &s_select[wave]);
     __syncthreads();
     stamp(5);
 }

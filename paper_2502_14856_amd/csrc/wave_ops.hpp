@@ -91,6 +91,62 @@ __device__ __forceinline__ float wave_sum_f32(float v) {
     return (a + b) + (c + d);
 }
 
+// ---- row (16 lanes) and half-wave (32 lanes) primitives ----
+// Butterfly reductions over a DPP row: every lane of the row receives the same bits.
+__device__ __forceinline__ unsigned row16_max_u32(unsigned v) {
+    v = max(v, (unsigned)dpp_i32<kDppQuadXor1>((int)v));
+    v = max(v, (unsigned)dpp_i32<kDppQuadXor2>((int)v));
+    v = max(v, (unsigned)dpp_i32<kDppRowHalfMirror>((int)v));
+    v = max(v, (unsigned)dpp_i32<kDppRowMirror>((int)v));
+    return v;
+}
+__device__ __forceinline__ unsigned row16_min_u32(unsigned v) {
+    v = min(v, (unsigned)dpp_i32<kDppQuadXor1>((int)v));
+    v = min(v, (unsigned)dpp_i32<kDppQuadXor2>((int)v));
+    v = min(v, (unsigned)dpp_i32<kDppRowHalfMirror>((int)v));
+    v = min(v, (unsigned)dpp_i32<kDppRowMirror>((int)v));
+    return v;
+}
+__device__ __forceinline__ float row16_max_f32(float v) {
+    v = fmaxf(v, dpp_f32<kDppQuadXor1>(v));
+    v = fmaxf(v, dpp_f32<kDppQuadXor2>(v));
+    v = fmaxf(v, dpp_f32<kDppRowHalfMirror>(v));
+    v = fmaxf(v, dpp_f32<kDppRowMirror>(v));
+    return v;
+}
+__device__ __forceinline__ float row16_sum_all(float v) {
+    v += dpp_f32<kDppQuadXor1>(v);
+    v += dpp_f32<kDppQuadXor2>(v);
+    v += dpp_f32<kDppRowHalfMirror>(v);
+    v += dpp_f32<kDppRowMirror>(v);
+    return v;
+}
+// Exchange with the lane 16 away inside each group of 32 lanes (crossbar only, no LDS
+// memory), and with the lane 32 away.
+constexpr int kSwizzleSwap16 = 0x401F;   // bit mode: and 0x1f, or 0, xor 0x10
+__device__ __forceinline__ unsigned swap16_u32(unsigned v) {
+    return (unsigned)__builtin_amdgcn_ds_swizzle((int)v, kSwizzleSwap16);
+}
+__device__ __forceinline__ float swap16_f32(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), kSwizzleSwap16));
+}
+__device__ __forceinline__ unsigned swap32_u32(unsigned v) {
+    return (unsigned)__builtin_amdgcn_ds_bpermute((lane_id() ^ 32) << 2, (int)v);
+}
+// The k-th largest (1 <= k <= 16, counted with multiplicity) of the 16 values held by the
+// lanes of a DPP row, returned to every lane of the row: the smallest value that has
+// fewer than k strictly larger ones.  Rows are independent of each other.
+template <int N>
+__device__ __forceinline__ int row16_count_greater(unsigned v) {
+    int c = (unsigned)dpp_i32<0x120 + N>((int)v) > v;   // row_ror:N
+    if constexpr (N > 1) c += row16_count_greater<N - 1>(v);
+    return c;
+}
+__device__ __forceinline__ unsigned row16_kth_largest_u32(unsigned v, int k) {
+    const int greater = row16_count_greater<15>(v);
+    return row16_min_u32(greater < k ? v : 0xFFFFFFFFu);
+}
+
 // (value, id) ordering of the candidate lists: larger value first, equal values by
 // lower token id.
 __device__ __forceinline__ bool cand_before(float va, int ida, float vb, int idb) {
@@ -120,7 +176,7 @@ __device__ __forceinline__ unsigned long long make_key(unsigned hi, unsigned lo)
 }
 
 // Per-wavefront LDS scratch of the threshold selection below.
-struct SelectScratch {
+struct alignas(16) SelectScratch {
     unsigned long long key[kWave];
     int pl[kWave];
 };
