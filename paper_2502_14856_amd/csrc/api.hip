@@ -26,11 +26,13 @@ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline size_t round256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
 
 struct WorkspaceLayout {
-    size_t ms_off, val_off, id_off, total;
+    size_t mail_rec_off, mail_st_off, ms_off, val_off, id_off, total;
     WorkspaceLayout(int64_t M, int32_t k) {
         const size_t rows = static_cast<size_t>(M < kMatrixPathMaxM ? M : kMatrixPathMaxM);
         const size_t slots = static_cast<size_t>(kWorkspaceGridMax) * rows;
         size_t o = kWorkspaceHeaderBytes;
+        mail_rec_off = o; o += kMailRecBytes;
+        mail_st_off = o;  o += kMailStBytes;
         ms_off = o;  o += round256(slots * 2 * sizeof(float));
         val_off = o; o += round256(slots * static_cast<size_t>(k) * sizeof(float));
         id_off = o;  o += round256(slots * static_cast<size_t>(k) * sizeof(int));
@@ -70,6 +72,8 @@ fr_status head_topk(const void *H, int64_t M, int64_t d, const void *W, const in
     p.V_rows = static_cast<int>(V_rows);
     p.k = k;
     p.ws.ticket = reinterpret_cast<unsigned *>(ws);
+    p.ws.mail_rec = reinterpret_cast<unsigned long long *>(ws + wl.mail_rec_off);
+    p.ws.mail_st = reinterpret_cast<unsigned long long *>(ws + wl.mail_st_off);
     p.ws.part_ms = reinterpret_cast<float *>(ws + wl.ms_off);
     p.ws.part_val = reinterpret_cast<float *>(ws + wl.val_off);
     p.ws.part_id = reinterpret_cast<int *>(ws + wl.id_off);
@@ -149,9 +153,14 @@ size_t fr_workspace_bytes(int64_t M, int64_t d, int64_t V_rows, int32_t k) {
 fr_status fr_workspace_init(void *workspace, size_t workspace_bytes, fr_stream stream) {
     if (!workspace) return FR_ERR_INVALID_ARG;
     if (!aligned16(workspace)) return FR_ERR_ALIGNMENT;
-    if (workspace_bytes < kWorkspaceHeaderBytes) return FR_ERR_WORKSPACE;
-    return launch_fill_u32(static_cast<unsigned *>(workspace), kWorkspaceHeaderBytes / 4, 0u,
-                           static_cast<hipStream_t>(stream));
+    const size_t mail = kMailRecBytes + kMailStBytes;
+    if (workspace_bytes < kWorkspaceHeaderBytes + mail) return FR_ERR_WORKSPACE;
+    // arrival words: zero; mailbox: all ones (= every record empty)
+    fr_status st = launch_fill_u32(static_cast<unsigned *>(workspace), kWorkspaceHeaderBytes / 4, 0u,
+                                   static_cast<hipStream_t>(stream));
+    if (st != FR_OK) return st;
+    return launch_fill_u32(reinterpret_cast<unsigned *>(static_cast<char *>(workspace) + kWorkspaceHeaderBytes),
+                           mail / 4, 0xFFFFFFFFu, static_cast<hipStream_t>(stream));
 }
 
 fr_status fr_draft_topk(const void *H, int64_t M, int64_t d, const void *W_sub,

@@ -41,6 +41,44 @@ template <typename T>
 __device__ __forceinline__ T observe(const T *p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+/*
+ * Mailbox of the skinny kernel's single-launch path: the same partial results as 8-byte
+ * records that say by themselves whether they have been written.  A record is all ones
+ * while empty; a workgroup fills its records with single 8-byte stores (whole or not at
+ * all for any reader), the merging workgroup polls the records it needs until none is
+ * empty, and empties them again once it has read them.  Between calls every record is
+ * empty, so no counter, no flag and no wait for a store to be acknowledged stands
+ * between a workgroup's last result and the merge.
+ *   rec[m][t][g]  list position t of row m from workgroup g: (value bits << 32) | id
+ *   st[m][g]      (running max bits << 32) | (sum-of-exp bits)
+ * A token id is never -1 and the statistics are canonicalised, so no real record is all ones.
+ */
+struct Mailbox {
+    unsigned long long *rec;
+    unsigned long long *st;
+};
+constexpr int kMailRows = 16, kMailK = 16;
+constexpr unsigned long long kMailEmpty = ~0ull;
+constexpr unsigned kMailSpinLimit = 1u << 20;   // rounds of about a microsecond before giving up
+__device__ __forceinline__ size_t mail_rec_index(int m, int t, int g) {
+    return (size_t)(m * kMailK + t) * kGridMax + g;
+}
+__device__ __forceinline__ size_t mail_st_index(int m, int g) { return (size_t)m * kGridMax + g; }
+__device__ __forceinline__ unsigned long long mail_pack(float hi, unsigned lo) {
+    return ((unsigned long long)__builtin_bit_cast(unsigned, hi) << 32) | lo;
+}
+__device__ __forceinline__ unsigned long long mail_pack_stats(float mx, float S) {
+    unsigned s = __builtin_bit_cast(unsigned, S);
+    if (s == 0xFFFFFFFFu) s = 0x7FC00000u;   // a NaN is a NaN; this one is taken
+    return mail_pack(mx, s);
+}
+__device__ __forceinline__ float mail_hi(unsigned long long r) {
+    return __builtin_bit_cast(float, (unsigned)(r >> 32));
+}
+__device__ __forceinline__ float mail_lo_f32(unsigned long long r) {
+    return __builtin_bit_cast(float, (unsigned)r);
+}
+
 // Blocks the wavefront until its outstanding stores have been acknowledged.
 __device__ __forceinline__ void wait_stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
@@ -266,16 +304,21 @@ __device__ __forceinline__ void lds_words(const T *p, T (&out)[C]) {
 }
 
 // Where a fold puts its results: the workgroup's running state in LDS, or, on the
-// workgroup's last pass, straight into the workspace (slot g of the partials).
+// workgroup's last pass, straight into the workspace (slot g of the partials, or of the
+// mailbox).
+enum class FoldTo : int { kLds = 0, kPartials = 1, kMailbox = 2 };
 struct FoldSink {
-    bool to_global;
+    FoldTo to;
     Partials part;
+    Mailbox mail;
     int g;
     float *run_ms;
     float *run_val;
     int *run_id;
     __device__ __forceinline__ void entry(int m, int k, int slot, float v, int id) const {
-        if (to_global) {
+        if (to == FoldTo::kMailbox) {
+            publish(mail.rec + mail_rec_index(m, slot, g), mail_pack(v, (unsigned)id));
+        } else if (to == FoldTo::kPartials) {
             publish(part.val + part_index(m * k + slot, g), v);
             publish(part.id + part_index(m * k + slot, g), id);
         } else {
@@ -284,7 +327,9 @@ struct FoldSink {
         }
     }
     __device__ __forceinline__ void stats(int m, float mx, float S) const {
-        if (to_global) {
+        if (to == FoldTo::kMailbox) {
+            publish(mail.st + mail_st_index(m, g), mail_pack_stats(mx, S));
+        } else if (to == FoldTo::kPartials) {
             publish(part.ms + part_index(m * 2, g), mx);
             publish(part.ms + part_index(m * 2 + 1, g), S);
         } else {
@@ -410,36 +455,30 @@ __device__ __forceinline__ bool fold_pair_fast(const float *z_lds, int ZR, int K
 }
 
 // General fold of one row by one whole wavefront, kept out of line: any k, any number of
-// tied values.  On the workgroup's last pass the row is also published.
+// tied values.  The row's state stays in LDS; on the workgroup's last pass it is also
+// written out.
 template <int ZR, bool WITH_RUN>
 __device__ __noinline__ void fold_row_general(FoldRow row, int KS, int z_slice_stride, const int *ids_pass,
-                                              int n_valid, int k, SelectScratch *sc, bool to_global,
-                                              Partials part, int m, int g) {
+                                              int n_valid, int k, SelectScratch *sc, FoldSink out, int m) {
     const FoldRow rows[1] = {row};
     block_fold_rows<ZR, 1, WITH_RUN>(rows, KS, z_slice_stride, ids_pass, n_valid, k, sc);
-    if (to_global) {
+    if (out.to != FoldTo::kLds) {
         const int lane = lane_id();
-        if (lane < k) {
-            publish(part.val + part_index(m * k + lane, g), row.run_val[lane]);
-            publish(part.id + part_index(m * k + lane, g), row.run_id[lane]);
-        }
-        if (lane < 2) publish(part.ms + part_index(m * 2 + lane, g), row.run_ms[lane]);
+        if (lane < k) out.entry(m, k, lane, row.run_val[lane], row.run_id[lane]);
+        if (lane == 0) out.stats(m, row.run_ms[0], row.run_ms[1]);
     }
 }
 
 /*
- * Folds one pass into the running state of all M rows of H; on the workgroup's last pass
- * (`to_global`) the result goes straight to slot g of the partials instead.  Wavefront w
- * of `waves` takes rows w and w + waves (then + 2 * waves, ...), two at a time in its two
- * halves while k <= 16.
+ * Folds one pass into the running state of all M rows of H, or, on the workgroup's last
+ * pass, writes the result out (see FoldSink).  Wavefront w of `waves` takes rows w and
+ * w + waves (then + 2 * waves, ...), two at a time in its two halves while k <= 16.
  */
 template <int ZR_MAX, bool WITH_RUN, typename RowOf>
 __device__ __forceinline__ void fold_pass(const float *z_lds, int ZR, int KS, int z_slice_stride,
                                           const int *ids_pass, int n_valid, int k, int M, int wave, int waves,
-                                          RowOf row_of, float *run_ms, float *run_val, int *run_id,
-                                          bool to_global, const Partials &part, int g, SelectScratch *sc) {
+                                          RowOf row_of, const FoldSink &out, SelectScratch *sc) {
     if (k <= kSmallKMax) {
-        const FoldSink out{to_global, part, g, run_ms, run_val, run_id};
         for (int mb = 0; mb < M; mb += 2 * waves) {
             const int m_lo = mb + wave, m_hi = mb + wave + waves;
             if (m_lo >= M) break;
@@ -447,16 +486,14 @@ __device__ __forceinline__ void fold_pass(const float *z_lds, int ZR, int KS, in
             if (fold_pair_fast<ZR_MAX, WITH_RUN>(z_lds, ZR, KS, z_slice_stride, ids_pass, n_valid, k, m, m < M,
                                                  out, sc))
                 continue;
-            fold_row_general<ZR_MAX, WITH_RUN>(row_of(m_lo), KS, z_slice_stride, ids_pass, n_valid, k, sc,
-                                               to_global, part, m_lo, g);
+            fold_row_general<ZR_MAX, WITH_RUN>(row_of(m_lo), KS, z_slice_stride, ids_pass, n_valid, k, sc, out, m_lo);
             if (m_hi < M)
-                fold_row_general<ZR_MAX, WITH_RUN>(row_of(m_hi), KS, z_slice_stride, ids_pass, n_valid, k, sc,
-                                                   to_global, part, m_hi, g);
+                fold_row_general<ZR_MAX, WITH_RUN>(row_of(m_hi), KS, z_slice_stride, ids_pass, n_valid, k, sc, out,
+                                                   m_hi);
         }
     } else {
         for (int m = wave; m < M; m += waves)
-            fold_row_general<ZR_MAX, WITH_RUN>(row_of(m), KS, z_slice_stride, ids_pass, n_valid, k, sc,
-                                               to_global, part, m, g);
+            fold_row_general<ZR_MAX, WITH_RUN>(row_of(m), KS, z_slice_stride, ids_pass, n_valid, k, sc, out, m);
     }
 }
 
@@ -711,21 +748,22 @@ __device__ __noinline__ void final_merge_general(Partials P, int G, int first, i
 }
 
 /*
- * A workgroup merges the G <= 256 partial results of rows first, first + stride, ... of H,
- * k <= 16.  One trip to memory per row.  Four wavefronts (one per SIMD; the others only
- * keep the barriers company) fetch the G list heads, for the bound, and entry t of all G
- * lists for the list positions t = wave, wave + 4, ...; the last of the four also fetches
- * the softmax statistics.  The groups of the bound are the 16 sets of heads
- * {g : g mod 16 = j}.  Each wavefront keeps those of its entries that reach the bound
- * (k plus a few survive, out of G * k: most registers hold none, and those are skipped),
- * the survivors meet in LDS, and the first wavefront ranks them and writes the outputs.
+ * A workgroup merges the G <= 256 mailbox records of rows first, first + stride, ... of H,
+ * k <= 16.  Four wavefronts (one per SIMD; the others only keep the barriers company)
+ * fetch, and keep fetching until none is empty: entry t of all G lists for the list
+ * positions t = wave, wave + 4, ...; the G list heads (position 0), for the bound; and,
+ * the last of the four, the softmax statistics.  The groups of the bound are the 16 sets
+ * of heads {g : g mod 16 = j}.  Each wavefront keeps those of its entries that reach the
+ * bound (k plus a few survive, out of G * k: most registers hold none, and those are
+ * skipped), the survivors meet in LDS, and the first wavefront ranks them and writes
+ * the outputs.  The records are emptied for the next call on the way.
  */
-__device__ __forceinline__ void merge_rows_fast(const Partials &P, int G, int first, int stride, int M, int k,
-                                                int *token_ids, float *logp, MergeScratch *ms,
-                                                SelectScratch *sc) {
+__device__ __forceinline__ void merge_rows_mailbox(const Mailbox &mb, const Partials &P, unsigned *error, int G,
+                                                   int first, int stride, int M, int k, int *token_ids,
+                                                   float *logp, MergeScratch *ms, SelectScratch *sc) {
     constexpr int HPL = 4;                      // G <= 256
     constexpr int NW = 4;                       // fetching wavefronts
-    constexpr int TPW = kSmallKMax / NW;        // list positions per fetching wavefront
+    constexpr int TPW = kMailK / NW;            // list positions per fetching wavefront
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x / kWave);
     for (int m = first; m < M; m += stride) {
@@ -734,35 +772,59 @@ __device__ __forceinline__ void merge_rows_fast(const Partials &P, int G, int fi
             if (lane == 0) ms->count = 0u;
         }
         __syncthreads();
+        unsigned long long ent[TPW][HPL], head[HPL], stt[HPL];
+        const unsigned long long *hrow = mb.rec + mail_rec_index(m, 0, 0);
+        const unsigned long long *srow = mb.st + mail_st_index(m, 0);
         if (wave < NW) {
-            // ---- every load of the row, unconditional from clamped addresses
-            float hv[HPL], ev[TPW][HPL], mxs[HPL], Ss[HPL];
-            int eid[TPW][HPL];
+            // ---- fetch until no record is empty; unconditional first round from clamped
+            // addresses, then only what is still missing
 #pragma unroll
             for (int q = 0; q < HPL; ++q) {
                 const int g = lane + kWave * q, gs = g < G ? g : G - 1;
-                hv[q] = observe(P.val + part_index(m * k, gs));
 #pragma unroll
                 for (int j = 0; j < TPW; ++j) {
                     const int t = wave + j * NW, ts = t < k ? t : 0;
-                    ev[j][q] = observe(P.val + part_index(m * k + ts, gs));
-                    eid[j][q] = observe(P.id + part_index(m * k + ts, gs));
+                    ent[j][q] = observe(mb.rec + mail_rec_index(m, ts, gs));
                 }
+                head[q] = observe(hrow + gs);
+                stt[q] = wave == NW - 1 ? observe(srow + gs) : 0ull;
             }
-            if (wave == NW - 1) {
+            for (unsigned polls = 0;; ++polls) {
+                bool again = false;
 #pragma unroll
                 for (int q = 0; q < HPL; ++q) {
-                    const int g = lane + kWave * q, gs = g < G ? g : G - 1;
-                    mxs[q] = observe(P.ms + part_index(m * 2, gs));
-                    Ss[q] = observe(P.ms + part_index(m * 2 + 1, gs));
+                    const int g = lane + kWave * q;
+                    const bool real_g = g < G;
+#pragma unroll
+                    for (int j = 0; j < TPW; ++j) {
+                        const int t = wave + j * NW;
+                        if (real_g && t < k && ent[j][q] == kMailEmpty) {
+                            ent[j][q] = observe(mb.rec + mail_rec_index(m, t, g));
+                            again = true;
+                        }
+                    }
+                    if (real_g && head[q] == kMailEmpty) {
+                        head[q] = observe(hrow + g);
+                        again = true;
+                    }
+                    if (real_g && stt[q] == kMailEmpty) {
+                        stt[q] = observe(srow + g);
+                        again = true;
+                    }
                 }
+                if (!__any(again)) break;
+                if (polls > kMailSpinLimit) {
+                    if (lane == 0) __hip_atomic_store(error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(1);
             }
 
             // ---- the bound (every fetching wavefront computes the same one).  Maxima are
             // taken as floats (a NaN head just does not take part) and ordered as keys.
             float lmax = kNegInf;
 #pragma unroll
-            for (int q = 0; q < HPL; ++q) lmax = fmaxf(lmax, lane + kWave * q < G ? hv[q] : kNegInf);
+            for (int q = 0; q < HPL; ++q) lmax = fmaxf(lmax, lane + kWave * q < G ? mail_hi(head[q]) : kNegInf);
             unsigned gm = key_hi_of(lmax);
             gm = max(gm, swap16_u32(gm));
             gm = max(gm, swap32_u32(gm));
@@ -774,8 +836,10 @@ __device__ __forceinline__ void merge_rows_fast(const Partials &P, int G, int fi
             for (int j = 0; j < TPW; ++j)
 #pragma unroll
                 for (int q = 0; q < HPL; ++q) {
-                    const bool real = (wave + j * NW < k) && (lane + kWave * q < G) && eid[j][q] != INT_MAX;
-                    const bool sv = real && !(ev[j][q] < bound);
+                    const int id = (int)(unsigned)ent[j][q];
+                    const float v = mail_hi(ent[j][q]);
+                    const bool real = (wave + j * NW < k) && (lane + kWave * q < G) && id != INT_MAX && id != -1;
+                    const bool sv = real && !(v < bound);
                     const unsigned long long mk = __ballot(sv);
                     if (mk != 0ull) {
                         unsigned base = 0u;
@@ -783,17 +847,18 @@ __device__ __forceinline__ void merge_rows_fast(const Partials &P, int G, int fi
                         const int pos = __builtin_amdgcn_readfirstlane((int)base) +
                                         (int)__builtin_amdgcn_mbcnt_hi((unsigned)(mk >> 32),
                                                                        __builtin_amdgcn_mbcnt_lo((unsigned)mk, 0u));
-                        if (sv && pos < kWave) ms->key[pos] = make_key(key_hi_of(ev[j][q]), ~(unsigned)eid[j][q]);
+                        if (sv && pos < kWave) ms->key[pos] = make_key(key_hi_of(v), ~(unsigned)id);
                     }
                 }
             if (wave == NW - 1) {
                 // log Z = mx + log sum_g S_g exp(mx_g - mx)
+                float mxs[HPL], Ss[HPL];
                 float lmx = kNegInf;
 #pragma unroll
                 for (int q = 0; q < HPL; ++q) {
                     const bool ok = lane + kWave * q < G;
-                    mxs[q] = ok ? mxs[q] : kNegInf;
-                    Ss[q] = ok ? Ss[q] : 0.0f;
+                    mxs[q] = ok ? mail_hi(stt[q]) : kNegInf;
+                    Ss[q] = ok ? mail_lo_f32(stt[q]) : 0.0f;
                     lmx = fmaxf(lmx, mxs[q]);
                 }
                 const float mx = wave_max_f32(lmx);
@@ -806,9 +871,26 @@ __device__ __forceinline__ void merge_rows_fast(const Partials &P, int G, int fi
         }
         __syncthreads();
 
-        if (wave == 0) {
-            const int n = __builtin_amdgcn_readfirstlane((int)ms->count);
-            if (n <= kWave) {
+        // ---- every wavefront has its records: empty them for the next call (each record
+        // by the wavefront that owns its list position; the statistics by the last one)
+        if (wave < NW) {
+#pragma unroll
+            for (int q = 0; q < HPL; ++q) {
+                const int g = lane + kWave * q;
+                if (g < G) {
+#pragma unroll
+                    for (int j = 0; j < TPW; ++j) {
+                        const int t = wave + j * NW;
+                        if (t < k) publish(mb.rec + mail_rec_index(m, t, g), kMailEmpty);
+                    }
+                    if (wave == NW - 1) publish(mb.st + mail_st_index(m, g), kMailEmpty);
+                }
+            }
+        }
+
+        const int n = __builtin_amdgcn_readfirstlane((int)ms->count);
+        if (n <= kWave) {
+            if (wave == 0) {
                 const unsigned long long mine = ms->key[lane];
                 const float logZ = ms->logZ;
                 const u64x2 *kp = reinterpret_cast<const u64x2 *>(ms->key);
@@ -827,9 +909,33 @@ __device__ __forceinline__ void merge_rows_fast(const Partials &P, int G, int fi
                     token_ids[(size_t)m * k + lane] = INT_MAX;
                     logp[(size_t)m * k + lane] = kNegInf;
                 }
-            } else {
-                final_merge_general(P, G, m, M, M, k, token_ids, logp, sc);   // this row only
             }
+        } else {
+            // Too many survivors (heavily tied values): hand the row to the general merge
+            // through the plain partial arrays.
+            if (wave < NW) {
+#pragma unroll
+                for (int q = 0; q < HPL; ++q) {
+                    const int g = lane + kWave * q;
+                    if (g < G) {
+#pragma unroll
+                        for (int j = 0; j < TPW; ++j) {
+                            const int t = wave + j * NW;
+                            if (t < k) {
+                                publish(P.val + part_index(m * k + t, g), mail_hi(ent[j][q]));
+                                publish(P.id + part_index(m * k + t, g), (int)(unsigned)ent[j][q]);
+                            }
+                        }
+                        if (wave == NW - 1) {
+                            publish(P.ms + part_index(m * 2, g), mail_hi(stt[q]));
+                            publish(P.ms + part_index(m * 2 + 1, g), mail_lo_f32(stt[q]));
+                        }
+                    }
+                }
+            }
+            wait_stores_done();
+            __syncthreads();
+            if (wave == 0) final_merge_general(P, G, m, M, M, k, token_ids, logp, sc);   // this row only
         }
     }
 }

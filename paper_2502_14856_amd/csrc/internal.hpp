@@ -11,7 +11,7 @@ namespace frspec {
 
 // What a contraction kernel does with the logits of a tile.
 enum class Sink : int {
-    kFusedTopk = 0,    // fold into partials; the last workgroup to arrive merges them
+    kFusedTopk = 0,    // fold into partials; some of the workgroups merge them (single launch)
     kPartialsOnly = 1, // fold into partials; a merge kernel follows
     kLogits = 2,       // store the logits (verification aid)
     kStreamOnly = 3,   // drop the logits (measures the contraction alone)
@@ -20,6 +20,8 @@ enum class Sink : int {
 // Device-side view of the workspace.
 struct WorkspaceView {
     unsigned *ticket;
+    unsigned long long *mail_rec;   // self-validating records of the skinny kernel
+    unsigned long long *mail_st;
     float *part_ms;
     float *part_val;
     int *part_id;
@@ -38,6 +40,10 @@ struct HeadProblem {
 };
 
 constexpr size_t kWorkspaceHeaderBytes = 512;
+// Mailbox of the skinny kernel: 16 rows of H x (16 list positions + 1 statistics record)
+// x 512 workgroups, 8 bytes each, all ones while empty.
+constexpr size_t kMailRecBytes = 16u * 16u * 512u * 8u;
+constexpr size_t kMailStBytes = 16u * 512u * 8u;
 constexpr int kWorkspaceGridMax = 512;   // partial slots reserved per row of H
 constexpr int kMatrixPathMaxM = 256;     // rows of H per matrix-core launch
 constexpr int kSkinnyMaxM = 16;          // rows of H the vector-ALU kernel covers

@@ -59,6 +59,7 @@ struct SkinnyArgs {
     int passes;           // ceil(V_rows / rows per pass)
     int sink;
     Partials part;
+    Mailbox mail;
     unsigned *ticket;
     int *token_ids;
     float *logp;
@@ -126,7 +127,9 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     stamp(0);
     // which arrival counter this call uses: asked for now, needed at the very end
     const Arrival ar(a.ticket);
-    const unsigned turn = a.sink == (int)Sink::kFusedTopk ? ar.turn() : 0u;
+    // single launch, k <= 16, at most 256 workgroups: results travel as mailbox records
+    const bool mailbox = a.sink == (int)Sink::kFusedTopk && a.k <= kSmallKMax && G <= 4 * kWave;
+    const unsigned turn = (a.sink == (int)Sink::kFusedTopk && !mailbox) ? ar.turn() : 0u;
 
     // Step range of this wavefront along d, split into a pipelined part (whole groups of
     // DEPTH full steps, no bounds handling at all) and leftovers (at most DEPTH - 1 steps,
@@ -367,14 +370,16 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
             auto row_of = [&](int m) {
                 return FoldRow{z_lds + m * ZR, run_ms + 2 * m, run_val + m * a.k, run_id + m * a.k};
             };
-            // the last pass of the workgroup publishes its result instead of keeping it
+            // the last pass of the workgroup writes its result out instead of keeping it
             const bool last = p + G >= a.passes;
+            const FoldSink out{!last ? FoldTo::kLds : (mailbox ? FoldTo::kMailbox : FoldTo::kPartials),
+                               part, a.mail, (int)blockIdx.x, run_ms, run_val, run_id};
             if (p == first_pass)
-                fold_pass<ZR_MAX, false>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, a.M, wave, WAVES, row_of,
-                                         run_ms, run_val, run_id, last, part, (int)blockIdx.x, &s_select[wave]);
+                fold_pass<ZR_MAX, false>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, a.M, wave, WAVES, row_of, out,
+                                         &s_select[wave]);
             else
-                fold_pass<ZR_MAX, true>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, a.M, wave, WAVES, row_of,
-                                        run_ms, run_val, run_id, last, part, (int)blockIdx.x, &s_select[wave]);
+                fold_pass<ZR_MAX, true>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, a.M, wave, WAVES, row_of, out,
+                                        &s_select[wave]);
         }
         if (p + G < a.passes) __syncthreads();
     }
@@ -383,15 +388,25 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     stamp(3);
     if (a.sink == (int)Sink::kPartialsOnly) return;
 
-    // ---- the first workgroups to arrive merge all partials (single launch) ----
+    // ---- some of the workgroups merge all partials (single launch) ----
     const int R = merger_count(G, a.M);
-    const int r = arrive_and_wait(ar, (unsigned)__builtin_amdgcn_readfirstlane((int)turn), G, R, &s_slot);
-    stamp(4);
-    if (r < 0) return;
-    if (a.k <= kSmallKMax && G <= 4 * kWave)
-        merge_rows_fast(part, G, r, R, a.M, a.k, a.token_ids, a.logp, &s_merge, &s_select[0]);
-    else
+    if (mailbox) {
+        // Mailbox records announce themselves: nothing to wait for, nothing to count.  The
+        // mergers are fixed, every 8th workgroup while there are enough (workgroups are
+        // dealt to the 8 dies in turn, so these share the first die), and start polling
+        // for the others' records as soon as their own are out.
+        const int spread = 8 * (R - 1) < G ? 8 : 1;
+        const int b = (int)blockIdx.x;
+        if (b % spread != 0 || b / spread >= R) return;
+        stamp(4);
+        merge_rows_mailbox(a.mail, part, a.ticket + 1, G, b / spread, R, a.M, a.k, a.token_ids, a.logp, &s_merge,
+                           &s_select[0]);
+    } else {
+        const int r = arrive_and_wait(ar, (unsigned)__builtin_amdgcn_readfirstlane((int)turn), G, R, &s_slot);
+        stamp(4);
+        if (r < 0) return;
         final_merge_general(part, G, r + R * wave, R * WAVES, a.M, a.k, a.token_ids, a.logp, &s_select[wave]);
+    }
     __syncthreads();
     stamp(5);
 }
@@ -535,6 +550,8 @@ fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hip
     a.part.val = p.ws.part_val;
     a.part.id = p.ws.part_id;
     a.ticket = p.ws.ticket;
+    a.mail.rec = p.ws.mail_rec;
+    a.mail.st = p.ws.mail_st;
     a.token_ids = p.token_ids;
     a.logp = p.logp;
     a.z_out = p.z_out;
