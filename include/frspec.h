@@ -77,8 +77,9 @@ fr_status fr_build_subset(const void *W_full, int64_t V, int64_t d,
 size_t fr_workspace_bytes(int64_t M, int64_t d, int64_t V_rows, int32_t k);
 
 /*
- * Prepares a freshly allocated workspace (clears the arrival counter that the fused
- * kernel uses to find the last workgroup).  Call once per workspace before its first use,
+ * Prepares a freshly allocated workspace: clears the arrival counters of the single-launch
+ * kernels and marks every record of the result mailbox empty (about 1.1 MiB is written).
+ * Call once per workspace before its first use,
  * and again if a call using it was ever abandoned mid-flight.  Every completed call
  * leaves the workspace ready for the next one.  Calls that share a workspace must be
  * ordered on one stream.
@@ -138,7 +139,7 @@ typedef struct fr_tuning {
                             1 = skinny kernel, products on the vector ALUs (bf16 dot2),
                             2 = chunked matrix-core kernel (any M) */
     int32_t two_launch;  /* 1 = merge the per-workgroup partials in a second launch instead
-                            of in the last workgroup to arrive (single launch) */
+                            of inside the same launch */
     int32_t variant;     /* skinny kernel build variant, 1-based (waves x pipeline depth x unit) */
     int32_t ksplit;      /* waves that share one 16-row tile along d (1, 2, 4, 8) */
     int32_t grid;        /* number of workgroups (<= 512) */

@@ -92,7 +92,7 @@ struct Arrival {
     unsigned *count;    // count[0] and count[32]
     __device__ explicit Arrival(unsigned *header) : parity(header), error(header + 1), count(header + 32) {}
     // Which counter this call uses; read by every workgroup when it starts.
-    __device__ unsigned turn() const { return __hip_atomic_load(parity, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & 1u; }
+    __device__ unsigned turn() const { return __hip_atomic_load(parity, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 };
 
 /*
@@ -118,6 +118,7 @@ __device__ __forceinline__ int arrive_and_wait(const Arrival &ar, unsigned turn,
     wait_stores_done();
     __syncthreads();
     if (threadIdx.x == 0) {
+        turn &= 1u;
         unsigned *mine = ar.count + 32 * turn;
         const unsigned a = __hip_atomic_fetch_add(mine, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (a == (unsigned)(G - 1)) {

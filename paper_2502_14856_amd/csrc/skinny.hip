@@ -17,8 +17,9 @@
 //     vector ALUs: packed bf16 dot products with fp32 accumulation in a 4-row x MT
 //     register tile, summed over the 16 lanes of a slot with DPP rotations at the end;
 //   * the tile's logits go to LDS, never to HBM, and are folded into the workgroup's
-//     running (max, sum-exp, top-k) state; the last workgroups to arrive merge the
-//     partials of all workgroups and write the outputs.
+//     running (max, sum-exp, top-k) state; on its last pass a workgroup writes that state
+//     to the workspace, where a few of the workgroups merge the results of all of them
+//     and write the outputs (for k <= 16 through self-validating mailbox records).
 // For small vocabularies several wavefronts share a tile and split d between them
 // (KS > 1) so that every compute unit still has enough loads in flight.
 #include "epilogue.hpp"
@@ -165,26 +166,18 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     // requested first and W right behind it: H can then be written to LDS while the first
     // W stages are still on their way, and the first products start as soon as W arrives.
     // Requested the other way round, H would queue behind 16 W loads per lane.
+    // Thread t fetches 16-byte column t of every row of H (wave-uniform base + 32-bit lane
+    // offset, like W), holds the pieces in registers and writes them to LDS further down.
     constexpr int NT = WAVES * kWave;
-    constexpr int kHPre = 12;   // 16-byte pieces of H per thread held in registers meanwhile
-    const int h_total = hrows * hpitch;
-    u32x4 hpre[kHPre];
-    {
-        // piece i = tid + u * NT sits at (row m, chunk c) of the padded H; advanced without
-        // dividing by the run-time pitch
-        int m = tid / hpitch, c = tid - m * hpitch;
+    constexpr int kHRowsMax = 16;
+    const GlobalBytes Hb = (GlobalBytes)a.H;
+    const unsigned hcol = (unsigned)min(tid, a.d8 - 1) * 16u;   // clamped: always a valid address
+    const unsigned hrow_bytes = (unsigned)a.d8 * 16u;
+    u32x4 hpre[kHRowsMax];
 #pragma unroll
-        for (int u = 0; u < kHPre; ++u) {
-            const bool real = m < a.M && m < hrows && c < a.d8;
-            const u32x4 v = a.H[real ? (size_t)m * a.d8 + c : 0];   // unconditional: loads stay back to back
-            hpre[u] = real ? v : zero_u32x4();
-            c += NT;
-            while (c >= hpitch) {
-                c -= hpitch;
-                ++m;
-            }
-        }
-    }
+    for (int m = 0; m < kHRowsMax; ++m)
+        if (m < hrows)   // wave-uniform; rows past M (zero padding) re-read the last row
+            hpre[m] = *reinterpret_cast<GlobalVec>(Hb + (unsigned)min(m, a.M - 1) * hrow_bytes + hcol);
     u32x4 wb[DEPTH][kRowsPerLane];
     unsigned wo[kRowsPerLane];
     const int first_pass = (int)blockIdx.x;
@@ -200,14 +193,15 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
 
     // stage H (zero padded to whole steps, and to MT rows where the tiles need it)
 #pragma unroll
-    for (int u = 0; u < kHPre; ++u)
-        if (tid + u * NT < h_total) H_lds[tid + u * NT] = hpre[u];
-    for (int i = tid + kHPre * NT; i < h_total; i += NT) {
-        const int m = i / hpitch, c = i - m * hpitch;
-        u32x4 v = zero_u32x4();
-        if (m < a.M && c < a.d8) v = a.H[(size_t)m * a.d8 + c];
-        H_lds[i] = v;
-    }
+    for (int m = 0; m < kHRowsMax; ++m)
+        if (m < hrows && tid < hpitch)
+            H_lds[m * hpitch + tid] = (tid < a.d8 && m < a.M) ? hpre[m] : zero_u32x4();
+    for (int c = tid + NT; c < hpitch; c += NT)   // columns past the first NT: not held in registers
+        for (int m = 0; m < hrows; ++m) {
+            u32x4 v = zero_u32x4();
+            if (m < a.M && c < a.d8) v = a.H[(size_t)m * a.d8 + c];
+            H_lds[m * hpitch + c] = v;
+        }
     // (the running state needs no reset: a workgroup's first pass overwrites all of it)
     __syncthreads();
     stamp(1);
