@@ -1,4 +1,4 @@
-"""ctypes front end of the CPU oracle (``frspec_oracle.c``).
+"""ctypes front end of the CPU oracle (``frspec_oracle.c``, ``beam_oracle.c``).
 
 TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by the smoke check and by the
 benchmark's cpu_baseline leg.  The GPU package never imports this module and
@@ -17,6 +17,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "frspec_oracle.c")
+_SRCS = [_SRC, os.path.join(_HERE, "beam_oracle.c")]
 _LIB = os.path.join(_HERE, "liboracle.so")
 
 _lib = None
@@ -24,9 +25,10 @@ _lib = None
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (-O2, OpenMP, no fast-math).  Returns the .so path."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    stale = not os.path.exists(_LIB) or any(os.path.getmtime(_LIB) < os.path.getmtime(src) for src in _SRCS)
+    if force or stale:
         cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-Wextra",
-               "-o", _LIB, _SRC, "-lm"]
+               "-o", _LIB, *_SRCS, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -45,9 +47,12 @@ def _load():
         lib.oracle_draft_topk.argtypes = [vp, i64, i64, vp, vp, i64, i32, vp, vp, vp]
         lib.oracle_full_topk.argtypes = [vp, i64, i64, vp, i64, i32, vp, vp, vp]
         lib.oracle_num_threads.argtypes = []
+        lib.oracle_beam_expand.argtypes = [vp, vp, i64, i32, vp, vp, i32, vp, vp, vp, i64, vp, vp, vp]
+        lib.oracle_tree_select.argtypes = [vp, vp, vp, i64, i32, vp, vp, vp, vp, vp]
         for name in ("oracle_build_subset", "oracle_logits_f32", "oracle_logits_f64",
                      "oracle_log_softmax", "oracle_topk", "oracle_draft_topk",
-                     "oracle_full_topk", "oracle_num_threads"):
+                     "oracle_full_topk", "oracle_num_threads", "oracle_beam_expand",
+                     "oracle_tree_select"):
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -163,3 +168,45 @@ def full_topk(H, W_full, k, want_logits=False):
     _check(_load().oracle_full_topk(_p(H), M, d, _p(W_full), V, k, _p(ids), _p(logp), _p(z)),
            "oracle_full_topk")
     return (ids, logp, z) if want_logits else (ids, logp)
+
+
+def beam_expand(logp, token_ids, node_score, node_hist, width, hist_score, hist_token, hist_parent,
+                hist_offset):
+    """One draft step of the beam search (Section 2).  Appends the M*k candidates to the history
+    arrays (in place, at hist_offset) and returns (next_score, next_token, next_hist) of the
+    `width` best."""
+    logp = np.ascontiguousarray(logp, dtype=np.float32)
+    token_ids = np.ascontiguousarray(token_ids, dtype=np.int32)
+    node_score = np.ascontiguousarray(node_score, dtype=np.float32)
+    node_hist = np.ascontiguousarray(node_hist, dtype=np.int32)
+    M, k = logp.shape
+    assert token_ids.shape == (M, k) and node_score.shape == (M,) and node_hist.shape == (M,)
+    for a, dt in ((hist_score, np.float32), (hist_token, np.int32), (hist_parent, np.int32)):
+        assert a.dtype == dt and a.flags.c_contiguous and a.shape[0] >= hist_offset + M * k
+    next_score = np.empty(width, dtype=np.float32)
+    next_token = np.empty(width, dtype=np.int32)
+    next_hist = np.empty(width, dtype=np.int32)
+    _check(_load().oracle_beam_expand(_p(logp), _p(token_ids), M, k, _p(node_score), _p(node_hist), width,
+                                      _p(hist_score), _p(hist_token), _p(hist_parent), hist_offset,
+                                      _p(next_score), _p(next_token), _p(next_hist)), "oracle_beam_expand")
+    return next_score, next_token, next_hist
+
+
+def tree_select(hist_score, hist_token, hist_parent, K):
+    """The draft tree: the K best history entries in history order, with the position of each
+    one's parent, its depth and the ancestor mask (Section 2).  Returns (sel_index, sel_token,
+    sel_parent, sel_depth, tree_mask[K, K] uint8)."""
+    hist_score = np.ascontiguousarray(hist_score, dtype=np.float32)
+    hist_token = np.ascontiguousarray(hist_token, dtype=np.int32)
+    hist_parent = np.ascontiguousarray(hist_parent, dtype=np.int32)
+    N = hist_score.shape[0]
+    assert hist_token.shape == (N,) and hist_parent.shape == (N,)
+    sel_index = np.empty(K, dtype=np.int32)
+    sel_token = np.empty(K, dtype=np.int32)
+    sel_parent = np.empty(K, dtype=np.int32)
+    sel_depth = np.empty(K, dtype=np.int32)
+    mask = np.empty((K, K), dtype=np.uint8)
+    _check(_load().oracle_tree_select(_p(hist_score), _p(hist_token), _p(hist_parent), N, K, _p(sel_index),
+                                      _p(sel_token), _p(sel_parent), _p(sel_depth), _p(mask)),
+           "oracle_tree_select")
+    return sel_index, sel_token, sel_parent, sel_depth, mask
