@@ -131,6 +131,54 @@ fr_status fr_draft_logits(const void *H, int64_t M, int64_t d,
                           const void *W, int64_t V_rows, float *z_out, fr_stream stream);
 
 /*
+ * One draft step of the beam search that drives the draft LM head (Section 2 of the paper:
+ * EAGLE-2 drafts by beam search on the draft model's softmax output).  The M nodes of the
+ * step (cumulative log-probability node_score[m]; node_hist[m] = index of the node in the
+ * search history, -1 for the prompt at the first step) have just received k candidates each
+ * from fr_draft_topk.  All M*k candidates are appended to the search history at
+ * hist_offset + c, c = m*k + j, with
+ *   hist_score  = node_score[m] + logp[m, j]      (one fp32 addition)
+ *   hist_token  = token_ids[m, j]
+ *   hist_parent = node_hist[m]
+ * and the `width` best of them (score descending, equal scores by lower c) are returned as
+ * the nodes of the next step: next_score, next_token, next_hist (= hist_offset + c).
+ *
+ *   logp, token_ids    in   fp32 / int32 [M, k] (the outputs of fr_draft_topk)
+ *   node_score         in   fp32 [M];  node_hist  in  int32 [M]
+ *   hist_*             io   fp32 / int32 / int32, at least hist_offset + M*k entries (caller's
+ *                           capacity; not checked)
+ *   next_*             out  [width], 1 <= width <= M*k
+ * All device pointers.  M*k <= 4096, else FR_ERR_UNSUPPORTED.  NaN scores are not ordered.
+ * Asynchronous on `stream`.
+ */
+fr_status fr_beam_expand(const float *logp, const int32_t *token_ids, int64_t M, int32_t k,
+                         const float *node_score, const int32_t *node_hist, int32_t width,
+                         float *hist_score, int32_t *hist_token, int32_t *hist_parent,
+                         int64_t hist_offset, float *next_score, int32_t *next_token,
+                         int32_t *next_hist, fr_stream stream);
+
+/*
+ * The draft tree (Section 2: "select the top K probability tokens from the beam search
+ * history"; "each token can only see tokens in its ancestral path").  Of the N history
+ * entries the K best (score descending, equal scores by lower index) are listed in ascending
+ * history index:
+ *   sel_index [K]     history index
+ *   sel_token [K]     token
+ *   sel_parent[K]     position (0..K-1) of the parent inside this list, -1 if the entry
+ *                     extends the prompt, -2 if its parent was not selected (cannot happen
+ *                     when a child never scores above its parent: log-probabilities <= 0)
+ *   sel_depth [K]     number of ancestors inside the list
+ *   tree_mask [K, K]  uint8, row p: 1 at p and at the positions of p's ancestors, else 0
+ * hist_parent[i] must be -1 or an index below i (entries are appended after their parents);
+ * a walk up the path stops at anything else.  All device pointers.  N <= 4096, K <= 1024,
+ * else FR_ERR_UNSUPPORTED.  Asynchronous on `stream`.
+ */
+fr_status fr_tree_select(const float *hist_score, const int32_t *hist_token,
+                         const int32_t *hist_parent, int64_t N, int32_t K, int32_t *sel_index,
+                         int32_t *sel_token, int32_t *sel_parent, int32_t *sel_depth,
+                         uint8_t *tree_mask, fr_stream stream);
+
+/*
  * Kernel-selection knobs for measurements and for tests that force one code path.
  * A zero in any field means "library default".
  */

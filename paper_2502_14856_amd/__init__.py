@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     FR_K_MAX,
     FrSpecError,
     Tuning,
+    fr_beam_expand,
     fr_build_subset,
     fr_calib_copy,
     fr_calib_read,
@@ -16,6 +17,7 @@ from .binding import (  # noqa: F401
     fr_draft_topk,
     fr_full_topk,
     fr_strerror,
+    fr_tree_select,
     fr_version,
     fr_workspace_bytes,
     fr_workspace_init,

@@ -63,10 +63,13 @@ def lib():
                                           ctypes.POINTER(Tuning)]
         L.fr_full_topk.argtypes = [vp, i64, i64, vp, i64, i32, vp, vp, vp, sz, vp]
         L.fr_draft_logits.argtypes = [vp, i64, i64, vp, i64, vp, vp]
+        L.fr_beam_expand.argtypes = [vp, vp, i64, i32, vp, vp, i32, vp, vp, vp, i64, vp, vp, vp, vp]
+        L.fr_tree_select.argtypes = [vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp]
         L.fr_calib_copy.argtypes = [vp, vp, sz, vp]
         L.fr_calib_read.argtypes = [vp, sz, vp, vp]
         for name in ("fr_build_subset", "fr_workspace_init", "fr_draft_topk", "fr_draft_topk_tuned",
-                     "fr_full_topk", "fr_draft_logits", "fr_calib_copy", "fr_calib_read"):
+                     "fr_full_topk", "fr_draft_logits", "fr_beam_expand", "fr_tree_select", "fr_calib_copy",
+                     "fr_calib_read"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -202,6 +205,62 @@ def fr_draft_logits(H, W, z_out=None, stream=None):
     _check(lib().fr_draft_logits(_ptr(H), M, d, _ptr(W), V_rows, _ptr(z_out), _stream(stream)),
            "fr_draft_logits")
     return z_out
+
+
+def _dev(t, dtype, name):
+    if not (t.is_cuda and t.is_contiguous() and t.dtype == dtype):
+        raise ValueError(f"{name} must be a contiguous CUDA tensor of {dtype}")
+    return t
+
+
+def fr_beam_expand(logp, token_ids, node_score, node_hist, width: int, hist_score, hist_token, hist_parent,
+                   hist_offset: int, next_score=None, next_token=None, next_hist=None, stream=None):
+    """One beam-search draft step (Section 2): appends the M*k candidates to the history at
+    hist_offset and returns (next_score, next_token, next_hist) of the `width` best."""
+    M, k = logp.shape
+    _dev(logp, torch.float32, "logp")
+    _dev(token_ids, torch.int32, "token_ids")
+    _dev(node_score, torch.float32, "node_score")
+    _dev(node_hist, torch.int32, "node_hist")
+    _dev(hist_score, torch.float32, "hist_score")
+    _dev(hist_token, torch.int32, "hist_token")
+    _dev(hist_parent, torch.int32, "hist_parent")
+    if token_ids.shape != (M, k) or node_score.numel() != M or node_hist.numel() != M:
+        raise ValueError("token_ids must be [M, k]; node_score and node_hist [M]")
+    if min(hist_score.numel(), hist_token.numel(), hist_parent.numel()) < hist_offset + M * k:
+        raise ValueError("history arrays are too short for hist_offset + M*k entries")
+    if next_score is None:
+        next_score = torch.empty(width, dtype=torch.float32, device=logp.device)
+    if next_token is None:
+        next_token = torch.empty(width, dtype=torch.int32, device=logp.device)
+    if next_hist is None:
+        next_hist = torch.empty(width, dtype=torch.int32, device=logp.device)
+    if min(next_score.numel(), next_token.numel(), next_hist.numel()) < width:
+        raise ValueError("next_* must hold `width` entries")
+    _check(lib().fr_beam_expand(_ptr(logp), _ptr(token_ids), M, k, _ptr(node_score), _ptr(node_hist), width,
+                                _ptr(hist_score), _ptr(hist_token), _ptr(hist_parent), hist_offset,
+                                _ptr(_dev(next_score, torch.float32, "next_score")),
+                                _ptr(_dev(next_token, torch.int32, "next_token")),
+                                _ptr(_dev(next_hist, torch.int32, "next_hist")), _stream(stream)),
+           "fr_beam_expand")
+    return next_score, next_token, next_hist
+
+
+def fr_tree_select(hist_score, hist_token, hist_parent, N: int, K: int, stream=None):
+    """The draft tree (Section 2): the K best of the first N history entries.  Returns
+    (sel_index, sel_token, sel_parent, sel_depth, tree_mask[K, K] uint8)."""
+    _dev(hist_score, torch.float32, "hist_score")
+    _dev(hist_token, torch.int32, "hist_token")
+    _dev(hist_parent, torch.int32, "hist_parent")
+    if min(hist_score.numel(), hist_token.numel(), hist_parent.numel()) < N:
+        raise ValueError("history arrays are shorter than N")
+    dev = hist_score.device
+    out = [torch.empty(K, dtype=torch.int32, device=dev) for _ in range(4)]
+    mask = torch.empty((K, K), dtype=torch.uint8, device=dev)
+    _check(lib().fr_tree_select(_ptr(hist_score), _ptr(hist_token), _ptr(hist_parent), N, K, _ptr(out[0]),
+                                _ptr(out[1]), _ptr(out[2]), _ptr(out[3]), _ptr(mask), _stream(stream)),
+           "fr_tree_select")
+    return out[0], out[1], out[2], out[3], mask
 
 
 def fr_calib_copy(dst, src, stream=None) -> None:

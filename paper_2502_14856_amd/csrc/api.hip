@@ -215,6 +215,35 @@ fr_status fr_draft_logits(const void *H, int64_t M, int64_t d, const void *W, in
     return FR_OK;
 }
 
+fr_status fr_beam_expand(const float *logp, const int32_t *token_ids, int64_t M, int32_t k,
+                         const float *node_score, const int32_t *node_hist, int32_t width,
+                         float *hist_score, int32_t *hist_token, int32_t *hist_parent,
+                         int64_t hist_offset, float *next_score, int32_t *next_token,
+                         int32_t *next_hist, fr_stream stream) {
+    if (!logp || !token_ids || !node_score || !node_hist || !hist_score || !hist_token || !hist_parent ||
+        !next_score || !next_token || !next_hist)
+        return FR_ERR_INVALID_ARG;
+    if (M < 1 || k < 1 || width < 1 || hist_offset < 0 || hist_offset > INT32_MAX) return FR_ERR_INVALID_ARG;
+    if (M > kGlueMaxCandidates || M * k > kGlueMaxCandidates) return FR_ERR_UNSUPPORTED;
+    if (width > M * k || hist_offset + M * k > INT32_MAX) return FR_ERR_INVALID_ARG;
+    return launch_beam_expand(logp, token_ids, static_cast<int>(M * k), k, node_score, node_hist, width,
+                              hist_score, hist_token, hist_parent, hist_offset, next_score, next_token,
+                              next_hist, static_cast<hipStream_t>(stream));
+}
+
+fr_status fr_tree_select(const float *hist_score, const int32_t *hist_token,
+                         const int32_t *hist_parent, int64_t N, int32_t K, int32_t *sel_index,
+                         int32_t *sel_token, int32_t *sel_parent, int32_t *sel_depth,
+                         uint8_t *tree_mask, fr_stream stream) {
+    if (!hist_score || !hist_token || !hist_parent || !sel_index || !sel_token || !sel_parent || !sel_depth ||
+        !tree_mask)
+        return FR_ERR_INVALID_ARG;
+    if (N < 1 || K < 1 || K > N) return FR_ERR_INVALID_ARG;
+    if (N > kGlueMaxCandidates || K > kGlueMaxTree) return FR_ERR_UNSUPPORTED;
+    return launch_tree_select(hist_score, hist_token, hist_parent, static_cast<int>(N), K, sel_index, sel_token,
+                              sel_parent, sel_depth, tree_mask, static_cast<hipStream_t>(stream));
+}
+
 fr_status fr_calib_copy(void *dst, const void *src, size_t bytes, fr_stream stream) {
     if (!dst || !src || (bytes % 16) != 0) return FR_ERR_INVALID_ARG;
     if (!aligned16(dst) || !aligned16(src)) return FR_ERR_ALIGNMENT;

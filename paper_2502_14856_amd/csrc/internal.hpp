@@ -70,6 +70,17 @@ fr_status launch_gather(const void *W_full, int64_t V, int64_t d, const int32_t 
                         int64_t V_sub, void *W_sub, int32_t *idx_map, int32_t *flag,
                         hipStream_t s);
 
+// glue.hip: beam-search expansion of one draft step and selection of the draft tree.
+constexpr int kGlueMaxCandidates = 4096;   // M * k of one step, and entries of a history
+constexpr int kGlueMaxTree = 1024;         // K
+fr_status launch_beam_expand(const float *logp, const int *token_ids, int C, int k, const float *node_score,
+                             const int *node_hist, int width, float *hist_score, int *hist_token,
+                             int *hist_parent, long long hist_offset, float *next_score, int *next_token,
+                             int *next_hist, hipStream_t s);
+fr_status launch_tree_select(const float *hist_score, const int *hist_token, const int *hist_parent, int N, int K,
+                             int *sel_index, int *sel_token, int *sel_parent, int *sel_depth,
+                             unsigned char *tree_mask, hipStream_t s);
+
 // calib.hip
 fr_status launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
 fr_status launch_read(const void *src, size_t bytes, void *sink, hipStream_t s);

@@ -118,3 +118,25 @@ def test_binding_refuses_cpu_tensors():
     W = torch.zeros((8, 64), dtype=torch.bfloat16)
     with pytest.raises(ValueError):
         fr.fr_draft_topk(H, W, None, 2, torch.zeros(1 << 20, dtype=torch.uint8))
+
+
+def test_beam_glue_rejects_bad_arguments_before_any_launch():
+    L = fr.lib()
+    UNSUPPORTED = -5
+    P = [0x1000 * (i + 1) for i in range(10)]
+
+    def expand(logp=P[0], tok=P[1], M=10, k=10, ns=P[2], nh=P[3], width=10, hs=P[4], ht=P[5], hp=P[6], off=0,
+               os_=P[7], ot=P[8], oh=P[9]):
+        return L.fr_beam_expand(logp, tok, M, k, ns, nh, width, hs, ht, hp, off, os_, ot, oh, None)
+
+    assert expand(logp=0) == INVALID and expand(oh=0) == INVALID and expand(hs=0) == INVALID
+    assert expand(M=0) == INVALID and expand(k=0) == INVALID and expand(width=0) == INVALID
+    assert expand(width=101) == INVALID and expand(off=-1) == INVALID
+    assert expand(M=65, k=64) == UNSUPPORTED          # more than 4096 candidates in one step
+
+    def select(hs=P[0], ht=P[1], hp=P[2], N=600, K=60, a=P[3], b=P[4], c=P[5], d=P[6], m=P[7]):
+        return L.fr_tree_select(hs, ht, hp, N, K, a, b, c, d, m, None)
+
+    assert select(hs=0) == INVALID and select(m=0) == INVALID
+    assert select(N=0) == INVALID and select(K=0) == INVALID and select(N=50, K=60) == INVALID
+    assert select(N=5000) == UNSUPPORTED and select(N=4096, K=2000) == UNSUPPORTED

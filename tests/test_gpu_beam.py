@@ -1,0 +1,114 @@
+"""GPU parity of the draft-step glue (beam expansion, draft-tree selection) against the CPU
+oracle: everything here is integer work or a single fp32 addition, so every output is
+compared bit for bit."""
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2502_14856_amd as fr
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _bits(a):
+    return np.ascontiguousarray(a).view(np.uint32)
+
+
+@pytest.mark.parametrize("seed,M,k,width,off", [(0, 1, 10, 10, 0), (1, 10, 10, 10, 10), (2, 10, 10, 100, 110),
+                                                (3, 16, 16, 7, 3), (4, 60, 10, 60, 0), (5, 64, 64, 333, 17),
+                                                (6, 1, 1, 1, 0)])
+def test_beam_expand_matches_oracle_bit_for_bit(seed, M, k, width, off):
+    _say("beam expand", seed, M, k, width, off)
+    rng = np.random.default_rng([20250214, 91, seed])
+    quantised = seed % 2 == 0          # exactly equal cumulative scores: the tie rule decides
+    logp = (-rng.integers(0, 12, size=(M, k)) / 4 if quantised else -rng.exponential(2.0, size=(M, k)))
+    logp = logp.astype(np.float32)
+    if seed == 3:
+        logp[:, -2:] = -np.inf         # rows with fewer than k real candidates
+    tok = rng.integers(0, 128256, size=(M, k)).astype(np.int32)
+    node_score = (-rng.integers(0, 8, size=M) / 2).astype(np.float32)
+    node_hist = rng.integers(-1, max(off, 1), size=M).astype(np.int32)
+    n = off + M * k
+    hs_o, ht_o, hp_o = np.full(n, 7.0, np.float32), np.full(n, 7, np.int32), np.full(n, 7, np.int32)
+    want = oracle.beam_expand(logp, tok, node_score, node_hist, width, hs_o, ht_o, hp_o, off)
+    hs_g, ht_g, hp_g = _dev(np.full(n, 7.0, np.float32)), _dev(np.full(n, 7, np.int32)), _dev(np.full(n, 7, np.int32))
+    got = fr.fr_beam_expand(_dev(logp), _dev(tok), _dev(node_score), _dev(node_hist), width, hs_g, ht_g, hp_g, off)
+    torch.cuda.synchronize()
+    assert np.array_equal(_bits(hs_g.cpu().numpy()), _bits(hs_o))
+    assert np.array_equal(ht_g.cpu().numpy(), ht_o) and np.array_equal(hp_g.cpu().numpy(), hp_o)
+    assert np.array_equal(_bits(got[0].cpu().numpy()), _bits(want[0]))
+    assert np.array_equal(got[1].cpu().numpy(), want[1]) and np.array_equal(got[2].cpu().numpy(), want[2])
+
+
+def _random_history(rng, n, quantised):
+    parent = np.empty(n, dtype=np.int32)
+    score = np.empty(n, dtype=np.float32)
+    for i in range(n):
+        parent[i] = -1 if i < min(n, 10) else int(rng.integers(-1, i))
+        step = -float(rng.integers(0, 6)) / 4 if quantised else -float(rng.exponential(1.0))
+        score[i] = np.float32((0.0 if parent[i] < 0 else score[parent[i]]) + np.float32(step))
+    return score, rng.integers(0, 128256, size=n).astype(np.int32), parent
+
+
+@pytest.mark.parametrize("seed,n,K", [(0, 40, 12), (1, 610, 60), (2, 610, 60), (3, 100, 100), (4, 1, 1),
+                                      (5, 4096, 128), (6, 1500, 1024), (7, 33, 32)])
+def test_tree_select_matches_oracle_bit_for_bit(seed, n, K):
+    _say("tree select", seed, n, K)
+    rng = np.random.default_rng([20250214, 92, seed])
+    score, token, parent = _random_history(rng, n, quantised=seed % 2 == 0)
+    want = oracle.tree_select(score, token, parent, K)
+    got = fr.fr_tree_select(_dev(score), _dev(token), _dev(parent), n, K)
+    torch.cuda.synchronize()
+    for g, w, name in zip(got, want, ("sel_index", "sel_token", "sel_parent", "sel_depth", "tree_mask")):
+        assert np.array_equal(g.cpu().numpy(), w), name
+
+
+def test_six_step_draft_with_the_lm_head_in_the_loop():
+    # the whole draft phase at the paper's setting (depth 6, 60 draft tokens; beam width 10 is
+    # this build's reading): fr_draft_topk -> fr_beam_expand per step, then fr_tree_select.
+    # The hidden state of a node is synthetic: a seeded function of (step, node).
+    from parity_utils import to_dev_bf16, to_dev_i32
+    from synth import make_hidden, make_weights, zipf_ranking
+    _say("six-step draft")
+    d, V, V_sub, k, width, depth, K = 256, 8192, 2048, 10, 10, 6, 60
+    W = make_weights(V, d, 0)
+    r, _ = zipf_ranking(V, 1.1, 10 ** 6, 0)
+    W_o, idx_o = oracle.build_subset(W, r, V_sub)
+    W_g, idx_g = fr.fr_build_subset(to_dev_bf16(W), to_dev_i32(r), V_sub)
+    ws = fr.new_workspace(width, d, V, k)
+    cap = k + (depth - 1) * width * k
+    hs_o, ht_o, hp_o = np.zeros(cap, np.float32), np.zeros(cap, np.int32), np.zeros(cap, np.int32)
+    hs_g, ht_g, hp_g = _dev(hs_o), _dev(ht_o), _dev(hp_o)
+    ns_o, nh_o = np.zeros(1, np.float32), np.full(1, -1, np.int32)
+    ns_g, nh_g = _dev(ns_o), _dev(nh_o)
+    off = 0
+    for step in range(depth):
+        M = len(ns_o)
+        H = make_hidden(M, d, 100 + step)
+        ids_o, lp_o = oracle.draft_topk(H, W_o, idx_o, k)
+        ids_g, lp_g = fr.fr_draft_topk(to_dev_bf16(H), W_g, idx_g, k, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(ids_g.cpu().numpy(), ids_o)
+        # the glue is compared on identical inputs: feed both sides the oracle's log-probabilities
+        ns_o, _, nh_o = oracle.beam_expand(lp_o, ids_o, ns_o, nh_o, min(width, M * k), hs_o, ht_o, hp_o, off)
+        ns_g, _, nh_g = fr.fr_beam_expand(_dev(lp_o), ids_g, ns_g, nh_g, min(width, M * k), hs_g, ht_g, hp_g, off)
+        off += M * k
+    assert off == cap
+    want = oracle.tree_select(hs_o, ht_o, hp_o, K)
+    got = fr.fr_tree_select(hs_g, ht_g, hp_g, off, K)
+    torch.cuda.synchronize()
+    assert np.array_equal(_bits(hs_g.cpu().numpy()), _bits(hs_o))
+    for g, w in zip(got, want):
+        assert np.array_equal(g.cpu().numpy(), w)
+    assert (want[2] != -2).all()            # every selected entry has its parent selected
+    assert int(want[3].max()) <= depth - 1
