@@ -142,6 +142,31 @@ def main() -> int:
     sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
     t_read = timed(lambda i: fr.fr_calib_read(copies[i % N_COPIES], sink), 200, 20)
 
+    # ---- the glue of a draft phase (Section 2: beam search, depth 6, 60 draft tokens; width 10)
+    width, depth, K = 10, 6, 60
+    cap = k + (depth - 1) * width * k
+    hist = (torch.zeros(cap, dtype=torch.float32, device="cuda"), torch.zeros(cap, dtype=torch.int32, device="cuda"),
+            torch.zeros(cap, dtype=torch.int32, device="cuda"))
+    node_score = torch.zeros(width, dtype=torch.float32, device="cuda")
+    node_hist = torch.full((width,), -1, dtype=torch.int32, device="cuda")
+    nxt = (torch.empty(width, dtype=torch.float32, device="cuda"), torch.empty(width, dtype=torch.int32, device="cuda"),
+           torch.empty(width, dtype=torch.int32, device="cuda"))
+    t_expand = timed(lambda i: fr.fr_beam_expand(logp, ids, node_score, node_hist, width, *hist, k,
+                                                 next_score=nxt[0], next_token=nxt[1], next_hist=nxt[2]), 300, 20)
+    # a history with real structure for the selection: one full draft phase
+    def draft_phase(i):
+        ns, nh, off = node_score[:1], node_hist[:1], 0
+        for step in range(depth):
+            Mstep = 1 if step == 0 else width
+            fr.fr_draft_topk(H[:Mstep], copies[(i * depth + step) % N_COPIES], idx_map, k, ws,
+                             token_ids=ids[:Mstep], logp=logp[:Mstep])
+            ns, _, nh = fr.fr_beam_expand(logp[:Mstep], ids[:Mstep], ns, nh, min(width, Mstep * k), *hist, off,
+                                          next_score=nxt[0], next_token=nxt[1], next_hist=nxt[2])
+            off += Mstep * k
+        return fr.fr_tree_select(*hist, off, K)
+    t_phase = timed(draft_phase, 100, 5)
+    t_select = timed(lambda i: fr.fr_tree_select(*hist, cap, K), 300, 20)
+
     bytes_per_call = V_sub * d * 2
     achieved = bytes_per_call / t_step / 1e9
     traffic = _profile_traffic()
@@ -195,6 +220,11 @@ def main() -> int:
             "full_over_subset_latency": t_full / t_step,
             "build_subset_us": t_build * 1e6,
             "build_subset_gbps_read_plus_write": 2 * bytes_per_call / t_build / 1e9,
+            "beam_expand_us": t_expand * 1e6,
+            "tree_select_us": t_select * 1e6,
+            "draft_phase_depth6_us": t_phase * 1e6,
+            "draft_phase_note": "6 x (fr_draft_topk + fr_beam_expand) + fr_tree_select (K=60), width 10; "
+                                "the draft model's transformer layer is not part of this build",
             "plain_read_kernel_us": t_read * 1e6,
             "plain_read_kernel_gbps": bytes_per_call / t_read / 1e9,
             "host_wall_s_timed_region": wall,

@@ -61,6 +61,11 @@ __global__ __launch_bounds__(kGlueThreads) void expand_kernel(
     }
 }
 
+constexpr int kGlueMaxN = kGlueMaxCandidates;
+static_assert(kGlueMaxN % kGlueThreads == 0 && kGlueMaxN / kWave == kWave, "one wavefront scans the chunk counts");
+constexpr int kGlueChunks = kGlueMaxN / kWave;                       // 64-entry chunks of a history
+constexpr int kGluePerThread = kGlueMaxN / kGlueThreads;
+
 __global__ __launch_bounds__(kGlueThreads) void tree_select_kernel(
     const float *__restrict__ hist_score, const int *__restrict__ hist_token,
     const int *__restrict__ hist_parent, int N, int K, int *__restrict__ sel_index,
@@ -69,40 +74,81 @@ __global__ __launch_bounds__(kGlueThreads) void tree_select_kernel(
     extern __shared__ u32x4 smem[];
     unsigned long long *keys = reinterpret_cast<unsigned long long *>(smem);   // [N + 2]
     int *posmap = reinterpret_cast<int *>(keys + ((N + 2) & ~1));              // [N]: position or -1
-    const int tid = threadIdx.x;
-    for (int i = tid; i < N; i += kGlueThreads) keys[i] = make_key(key_hi_of(hist_score[i]), ~(unsigned)i);
+    int *par = posmap + N;                                                     // [N]: hist_parent
+    __shared__ int chunk_before[kGlueChunks];   // selected entries before each 64-entry chunk
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    for (int i = tid; i < N; i += kGlueThreads) {
+        keys[i] = make_key(key_hi_of(hist_score[i]), ~(unsigned)i);
+        par[i] = hist_parent[i];
+    }
     if (tid == 0) keys[N] = 0ull;
+    if (tid < kGlueChunks) chunk_before[tid] = 0;
     for (int i = tid; i < K * K; i += kGlueThreads) tree_mask[i] = 0;
     __syncthreads();
-    // selected = fewer than K better entries
-    for (int i = tid; i < N; i += kGlueThreads) posmap[i] = count_greater(keys, N, keys[i]) < K ? 0 : -1;
+
+    // rank[i] = number of better entries.  A short history is scanned by several threads per
+    // entry (P of them share the keys between them), a long one by one thread per entry.
+    int *rank = par + N;   // [N]
+    for (int i = tid; i < N; i += kGlueThreads) rank[i] = 0;
     __syncthreads();
-    // position in history order = number of selected entries before this one
-    int my_pos[(4096 + kGlueThreads - 1) / kGlueThreads];
-    for (int i = tid, u = 0; i < N; i += kGlueThreads, ++u) {
-        int pos = -1;
-        if (posmap[i] == 0) {
-            pos = 0;
-            for (int j = 0; j < i; ++j) pos += posmap[j] == 0;
+    int P = 1;
+    while (P < 16 && 2 * P * N <= kGlueThreads) P *= 2;
+    if (P > 1) {
+        const int i = tid / P, part = tid - i * P;
+        if (i < N) {
+            const int per = ((N + P - 1) / P + 1) & ~1;   // even, so that reads stay 16-byte aligned
+            const int lo = part * per, hi = lo + per < N ? lo + per : N;
+            if (lo < hi) atomicAdd(&rank[i], count_greater(keys + lo, hi - lo, keys[i]));
         }
-        my_pos[u] = pos;
+    } else {
+        for (int i = tid; i < N; i += kGlueThreads) rank[i] = count_greater(keys, N, keys[i]);
     }
     __syncthreads();
-    for (int i = tid, u = 0; i < N; i += kGlueThreads, ++u) posmap[i] = my_pos[u];
+    // selected = fewer than K better entries.  Entry i = tid + u * 1024 lies in chunk i / 64,
+    // which one wavefront covers with one ballot.
+    int before_in_chunk[kGluePerThread];
+    bool selected[kGluePerThread];
+#pragma unroll
+    for (int u = 0; u < kGluePerThread; ++u) {
+        const int i = tid + u * kGlueThreads;
+        selected[u] = i < N && rank[i < N ? i : 0] < K;
+        const unsigned long long mask = __ballot(selected[u]);
+        before_in_chunk[u] = (int)__builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32),
+                                                             __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u));
+        if (lane == 0) chunk_before[i / kWave] = (int)__popcll(mask);
+    }
+    __syncthreads();
+    if (tid < kWave) {   // exclusive prefix sum over the 64 chunk counts, in one wavefront
+        const int own = chunk_before[tid];
+        int incl = own;
+#pragma unroll
+        for (int sh = 1; sh < kWave; sh <<= 1) {
+            const int other = __shfl_up(incl, sh);
+            if (lane >= sh) incl += other;
+        }
+        chunk_before[tid] = incl - own;
+    }
+    __syncthreads();
+    // position in history order = number of selected entries before this one
+#pragma unroll
+    for (int u = 0; u < kGluePerThread; ++u) {
+        const int i = tid + u * kGlueThreads;
+        if (i < N) posmap[i] = selected[u] ? chunk_before[i / kWave] + before_in_chunk[u] : -1;
+    }
     __syncthreads();
     for (int i = tid; i < N; i += kGlueThreads) {
         const int p = posmap[i];
         if (p < 0) continue;
         sel_index[p] = i;
         sel_token[p] = hist_token[i];
-        const int h = hist_parent[i];
+        const int h = par[i];
         // -1: extends the prompt; -2: parent not selected (impossible while no child scores
         // above its parent)
         sel_parent[p] = h < 0 ? -1 : (h < i && posmap[h] >= 0 ? posmap[h] : -2);
         tree_mask[(size_t)p * K + p] = 1;
         int depth = 0;
         // up the ancestral path; parents precede children, which also bounds the walk
-        for (int q = h, below = i; q >= 0 && q < below && posmap[q] >= 0; below = q, q = hist_parent[q]) {
+        for (int q = h, below = i; q >= 0 && q < below && posmap[q] >= 0; below = q, q = par[q]) {
             tree_mask[(size_t)p * K + posmap[q]] = 1;
             ++depth;
         }
@@ -126,7 +172,16 @@ fr_status launch_beam_expand(const float *logp, const int *token_ids, int C, int
 fr_status launch_tree_select(const float *hist_score, const int *hist_token, const int *hist_parent, int N, int K,
                              int *sel_index, int *sel_token, int *sel_parent, int *sel_depth,
                              unsigned char *tree_mask, hipStream_t s) {
-    const size_t lds = ((size_t)((N + 2) & ~1)) * sizeof(unsigned long long) + (size_t)N * sizeof(int);
+    const size_t lds = ((size_t)((N + 2) & ~1)) * sizeof(unsigned long long) + 3 * (size_t)N * sizeof(int);
+    static bool attr_done = false;   // up to 80 KiB + 16 B of dynamic LDS: above the default limit
+    if (!attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(tree_select_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024) != hipSuccess) {
+            (void)hipGetLastError();
+            return FR_ERR_HIP;
+        }
+        attr_done = true;
+    }
     hipLaunchKernelGGL(tree_select_kernel, dim3(1), dim3(kGlueThreads), lds, s, hist_score, hist_token,
                        hist_parent, N, K, sel_index, sel_token, sel_parent, sel_depth, tree_mask);
     return hip_status(hipGetLastError());
