@@ -207,6 +207,33 @@ fr_status fr_draft_topk_tuned(const void *H, int64_t M, int64_t d,
                               const fr_tuning *tuning);
 
 /*
+ * The same subset and the same head with W_sub in a private tiled layout (Eq. 3 fixes the
+ * matrix, not how it is stored; the gather rewrites W once anyway).  A tile is 16
+ * consecutive rows of W_sub; inside a tile, the 16-byte chunk holding row i (0..15),
+ * elements 32*kb + 8*g .. + 7 (g = 0..3) is chunk number kb*64 + g*16 + i, i.e. element
+ * (row r, column c) of W_sub is the bf16 at
+ *   (r / 16) * 16 * d  +  (c / 32) * 512  +  ((c % 32) / 8) * 128  +  (r % 16) * 8  +  c % 8.
+ * Every 1 KiB block is then one matrix-core operand in lane order: the kernel reads W in
+ * contiguous 4 KiB pieces and needs no reordering on chip.  Rows that pad the last tile are
+ * zero.  d must be a multiple of 128.
+ *   fr_tiled_bytes         size of W_tiled in bytes (0 if the arguments are invalid)
+ *   fr_build_subset_tiled  as fr_build_subset, writing W_tiled; a row whose id is outside
+ *                          [0, V) is zero, idx_map = -1, *dev_error_flag set
+ *   fr_draft_topk_tiled    as fr_draft_topk, reading W_tiled; M <= 16 (FR_ERR_UNSUPPORTED
+ *                          beyond); `tuning` may be NULL
+ */
+size_t fr_tiled_bytes(int64_t V_sub, int64_t d);
+fr_status fr_build_subset_tiled(const void *W_full, int64_t V, int64_t d,
+                                const int32_t *freq_ranked_ids, int64_t V_sub, void *W_tiled,
+                                int32_t *idx_map, int32_t *dev_error_flag, fr_stream stream);
+fr_status fr_draft_topk_tiled(const void *H, int64_t M, int64_t d, const void *W_tiled,
+                              const int32_t *idx_map, int64_t V_sub, int32_t k,
+                              int32_t *token_ids, float *logp, void *workspace,
+                              size_t workspace_bytes, fr_stream stream,
+                              const fr_tuning *tuning);
+
+
+/*
  * Bandwidth calibration kernels: a plain copy and a plain read of `bytes` bytes
  * (multiple of 16), used to scale hardware counters and to report what a trivial
  * streaming kernel achieves on the same machine.  `sink` receives one 16-byte value

@@ -11,12 +11,15 @@ from .binding import (  # noqa: F401
     Tuning,
     fr_beam_expand,
     fr_build_subset,
+    fr_build_subset_tiled,
     fr_calib_copy,
     fr_calib_read,
     fr_draft_logits,
     fr_draft_topk,
+    fr_draft_topk_tiled,
     fr_full_topk,
     fr_strerror,
+    fr_tiled_bytes,
     fr_tree_select,
     fr_version,
     fr_workspace_bytes,

@@ -63,12 +63,18 @@ def lib():
                                           ctypes.POINTER(Tuning)]
         L.fr_full_topk.argtypes = [vp, i64, i64, vp, i64, i32, vp, vp, vp, sz, vp]
         L.fr_draft_logits.argtypes = [vp, i64, i64, vp, i64, vp, vp]
+        L.fr_tiled_bytes.argtypes = [i64, i64]
+        L.fr_tiled_bytes.restype = sz
+        L.fr_build_subset_tiled.argtypes = [vp, i64, i64, vp, i64, vp, vp, vp, vp]
+        L.fr_draft_topk_tiled.argtypes = [vp, i64, i64, vp, vp, i64, i32, vp, vp, vp, sz, vp,
+                                          ctypes.POINTER(Tuning)]
         L.fr_beam_expand.argtypes = [vp, vp, i64, i32, vp, vp, i32, vp, vp, vp, i64, vp, vp, vp, vp]
         L.fr_tree_select.argtypes = [vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp]
         L.fr_calib_copy.argtypes = [vp, vp, sz, vp]
         L.fr_calib_read.argtypes = [vp, sz, vp, vp]
         for name in ("fr_build_subset", "fr_workspace_init", "fr_draft_topk", "fr_draft_topk_tuned",
-                     "fr_full_topk", "fr_draft_logits", "fr_beam_expand", "fr_tree_select", "fr_calib_copy",
+                     "fr_full_topk", "fr_draft_logits", "fr_beam_expand", "fr_tree_select", "fr_build_subset_tiled",
+                     "fr_draft_topk_tiled", "fr_calib_copy",
                      "fr_calib_read"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -205,6 +211,49 @@ def fr_draft_logits(H, W, z_out=None, stream=None):
     _check(lib().fr_draft_logits(_ptr(H), M, d, _ptr(W), V_rows, _ptr(z_out), _stream(stream)),
            "fr_draft_logits")
     return z_out
+
+
+def fr_tiled_bytes(V_sub: int, d: int) -> int:
+    return int(lib().fr_tiled_bytes(V_sub, d))
+
+
+def fr_build_subset_tiled(W_full, freq_ranked_ids, V_sub: int, W_tiled=None, idx_map=None,
+                          dev_error_flag=None, stream=None):
+    """Eq. 3 into the private tiled layout (see frspec.h).  Returns (W_tiled, idx_map);
+    W_tiled is a flat bf16 tensor of fr_tiled_bytes(V_sub, d) / 2 elements."""
+    _bf16_matrix(W_full, "W_full")
+    V, d = W_full.shape
+    n = fr_tiled_bytes(V_sub, d)
+    if n == 0:
+        raise ValueError("the tiled layout needs d to be a multiple of 128")
+    if W_tiled is None:
+        W_tiled = torch.empty(n // 2, dtype=W_full.dtype, device=W_full.device)
+    if idx_map is None:
+        idx_map = torch.empty(V_sub, dtype=torch.int32, device=W_full.device)
+    if W_tiled.numel() * W_tiled.element_size() < n or not W_tiled.is_contiguous():
+        raise ValueError("W_tiled is too small")
+    _check(lib().fr_build_subset_tiled(_ptr(W_full), V, d, _ptr(freq_ranked_ids), V_sub, _ptr(W_tiled),
+                                       _ptr(idx_map), _ptr(dev_error_flag), _stream(stream)),
+           "fr_build_subset_tiled")
+    return W_tiled, idx_map
+
+
+def fr_draft_topk_tiled(H, W_tiled, idx_map, V_sub: int, k: int, workspace, token_ids=None, logp=None,
+                        stream=None, tuning=None):
+    """fr_draft_topk on a W_sub in the tiled layout."""
+    _bf16_matrix(H, "H")
+    M, d = H.shape
+    if W_tiled.numel() * W_tiled.element_size() < fr_tiled_bytes(V_sub, d) or fr_tiled_bytes(V_sub, d) == 0:
+        raise ValueError("W_tiled does not hold V_sub rows of d elements in the tiled layout")
+    if token_ids is None:
+        token_ids = torch.empty((M, k), dtype=torch.int32, device=H.device)
+    if logp is None:
+        logp = torch.empty((M, k), dtype=torch.float32, device=H.device)
+    _check(lib().fr_draft_topk_tiled(_ptr(H), M, d, _ptr(W_tiled), _ptr(idx_map), V_sub, k, _ptr(token_ids),
+                                     _ptr(logp), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                     _stream(stream), ctypes.byref(tuning) if tuning is not None else None),
+           "fr_draft_topk_tiled")
+    return token_ids, logp
 
 
 def _dev(t, dtype, name):

@@ -53,7 +53,7 @@ fr_status check_head_args(const void *H, int64_t M, int64_t d, const void *W, in
 
 fr_status head_topk(const void *H, int64_t M, int64_t d, const void *W, const int32_t *idx_map,
                     int64_t V_rows, int32_t k, int32_t *token_ids, float *logp, void *workspace,
-                    size_t workspace_bytes, fr_stream stream, const fr_tuning *tuning) {
+                    size_t workspace_bytes, fr_stream stream, const fr_tuning *tuning, bool tiled = false) {
     fr_status st = check_head_args(H, M, d, W, V_rows, k);
     if (st != FR_OK) return st;
     if (!token_ids || !logp || !workspace) return FR_ERR_INVALID_ARG;
@@ -67,6 +67,7 @@ fr_status head_topk(const void *H, int64_t M, int64_t d, const void *W, const in
     char *ws = static_cast<char *>(workspace);
     HeadProblem p{};
     p.W = W;
+    p.tiled = tiled;
     p.idx_map = idx_map;
     p.d = static_cast<int>(d);
     p.V_rows = static_cast<int>(V_rows);
@@ -82,6 +83,10 @@ fr_status head_topk(const void *H, int64_t M, int64_t d, const void *W, const in
     // paths: 3 = skinny kernel on the matrix cores, 1 = skinny kernel on the vector ALUs,
     // 2 = chunked matrix-core kernel (any M)
     int path = tuning ? tuning->path : 0;
+    if (tiled) {   // only the skinny kernel's matrix-core build reads the tiled layout
+        if (path == 1 || path == 2 || M > kSkinnyMaxM || (d % 128) != 0) return FR_ERR_UNSUPPORTED;
+        path = 3;
+    }
     if (path == 0) path = (M <= kSkinnyMaxM && skinny_fits((int)M, (int)d, k)) ? 3 : 2;
     const bool two_launch = tuning && tuning->two_launch;
     const bool stream_only = tuning && tuning->stream_only;
@@ -143,6 +148,30 @@ fr_status fr_build_subset(const void *W_full, int64_t V, int64_t d, const int32_
     if (!aligned16(W_full) || !aligned16(W_sub)) return FR_ERR_ALIGNMENT;
     return launch_gather(W_full, V, d, freq_ranked_ids, V_sub, W_sub, idx_map, dev_error_flag,
                          static_cast<hipStream_t>(stream));
+}
+
+size_t fr_tiled_bytes(int64_t V_sub, int64_t d) {
+    if (V_sub < 1 || d < 128 || (d % 128) != 0) return 0;
+    return static_cast<size_t>((V_sub + 15) / 16) * 16u * static_cast<size_t>(d) * 2u;
+}
+
+fr_status fr_build_subset_tiled(const void *W_full, int64_t V, int64_t d, const int32_t *freq_ranked_ids,
+                                int64_t V_sub, void *W_tiled, int32_t *idx_map, int32_t *dev_error_flag,
+                                fr_stream stream) {
+    if (!W_full || !freq_ranked_ids || !W_tiled || !idx_map) return FR_ERR_INVALID_ARG;
+    if (V < 1 || V > INT32_MAX || d < 128 || (d % 128) != 0 || d > (1 << 24)) return FR_ERR_INVALID_ARG;
+    if (V_sub < 1 || V_sub > V) return FR_ERR_INVALID_ARG;
+    if (!aligned16(W_full) || !aligned16(W_tiled)) return FR_ERR_ALIGNMENT;
+    return launch_gather_tiled(W_full, V, d, freq_ranked_ids, V_sub, W_tiled, idx_map, dev_error_flag,
+                               static_cast<hipStream_t>(stream));
+}
+
+fr_status fr_draft_topk_tiled(const void *H, int64_t M, int64_t d, const void *W_tiled,
+                              const int32_t *idx_map, int64_t V_sub, int32_t k, int32_t *token_ids,
+                              float *logp, void *workspace, size_t workspace_bytes, fr_stream stream,
+                              const fr_tuning *tuning) {
+    return head_topk(H, M, d, W_tiled, idx_map, V_sub, k, token_ids, logp, workspace, workspace_bytes, stream,
+                     tuning, true);
 }
 
 size_t fr_workspace_bytes(int64_t M, int64_t d, int64_t V_rows, int32_t k) {

@@ -29,7 +29,8 @@ struct WorkspaceView {
 
 struct HeadProblem {
     const void *H;        // bf16 [M, d]
-    const void *W;        // bf16 [V_rows, d]
+    const void *W;        // bf16 [V_rows, d] row-major, or the tiled layout of fr_build_subset_tiled
+    bool tiled;
     const int *idx_map;   // nullable
     int M, d, V_rows, k;
     int *token_ids;       // [M, k]
@@ -66,6 +67,9 @@ int mfma_max_rows(int k);
 fr_status launch_merge(const HeadProblem &p, int G, hipStream_t s);
 
 // gather.hip
+fr_status launch_gather_tiled(const void *W_full, int64_t V, int64_t d, const int32_t *ids,
+                              int64_t V_sub, void *W_tiled, int32_t *idx_map, int32_t *flag,
+                              hipStream_t s);
 fr_status launch_gather(const void *W_full, int64_t V, int64_t d, const int32_t *ids,
                         int64_t V_sub, void *W_sub, int32_t *idx_map, int32_t *flag,
                         hipStream_t s);

@@ -54,6 +54,7 @@ struct SkinnyArgs {
     const u32x4 *W;
     const int *idx_map;
     int M, d8, V_rows, k;
+    int tiles;            // 16-row tiles of W (tiled layout only)
     int KS;               // wavefronts sharing one tile along d
     int steps;            // ceil(d8 / 16): steps of 128 elements along d
     int steps_per_split;  // ceil(steps / KS)
@@ -78,10 +79,10 @@ struct SkinnyLds {
     int h_off, stage_off, z_off, ids_off, ms_off, val_off, id_off, total;
     // `hrows` rows of H are staged: all MT (zero padded) for the dot-product variant, whose
     // register tiles are MT wide; only the M real ones for the matrix-core variant.
-    __host__ __device__ SkinnyLds(int MT, int hrows, int waves, int steps, int k, bool mfma) {
+    __host__ __device__ SkinnyLds(int MT, int hrows, int waves, int steps, int k, bool mfma, bool tiled) {
         int o = 0;
-        h_off = o;   o += hrows * steps * kLanesAlongD * 16;
-        stage_off = o; o += mfma ? waves * kTileRows * kStagePitch16 * 16 : 0;
+        h_off = o;   o += hrows * (steps * kLanesAlongD + 1) * 16;
+        stage_off = o; o += (mfma && !tiled) ? waves * kTileRows * kStagePitch16 * 16 : 0;
         z_off = o;   o += (waves * kTileRows * MT + waves * kTileRows) * 4;
         ids_off = o; o += waves * kTileRows * 4;
         ms_off = o;  o += MT * 2 * 4;
@@ -91,12 +92,13 @@ struct SkinnyLds {
     }
 };
 
-template <int MT, int WAVES, int DEPTH, bool MFMA>
+template <int MT, int WAVES, int DEPTH, bool MFMA, bool TILED = false>
 __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
+    static_assert(MFMA || !TILED, "the tiled layout is the matrix cores' operand order");
     extern __shared__ u32x4 smem[];
     char *base = reinterpret_cast<char *>(smem);
     const int hrows = MFMA ? a.M : MT;
-    const SkinnyLds L(MT, hrows, WAVES, a.steps, a.k, MFMA);
+    const SkinnyLds L(MT, hrows, WAVES, a.steps, a.k, MFMA, TILED);
     u32x4 *H_lds = reinterpret_cast<u32x4 *>(base + L.h_off);
     u32x4 *stage_lds = reinterpret_cast<u32x4 *>(base + L.stage_off);
     float *z_lds = reinterpret_cast<float *>(base + L.z_off);
@@ -116,7 +118,11 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // wave-uniform by construction
     const int lk = lane & (kLanesAlongD - 1);
     const int rs = lane / kLanesAlongD;
-    const int hpitch = a.steps * kStep16;        // 16-byte chunks per padded row of H
+    // 16-byte chunks per row of H in LDS: the row padded to whole steps, plus one chunk so
+    // that the rows start 4 banks apart (the matrix-core fragments are read down a column of
+    // H: lanes l % 16 = row; without the skew all rows of a column share their banks)
+    const int hcols = a.steps * kStep16;
+    const int hpitch = hcols + 1;
     const int KS = a.KS;
     const int ZR = (WAVES / KS) * kTileRows;     // vocabulary rows per pass
     const int tile_in_pass = wave / KS;
@@ -150,16 +156,28 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     // W is addressed as a wave-uniform base plus a per-lane 32-bit byte offset (the host
     // guarantees the matrix is smaller than 4 GiB): offset of (row, chunk lk of step
     // s_begin) for the 4 rows of this lane.
+    // Tiled layout: a 16-row tile of W is one contiguous run of 1 KiB blocks, one per 32
+    // elements of d, each block already in the lane order of the matrix cores' A operand
+    // (lane l: row l % 16, elements 8 * (l / 16) .. + 7 of the block).  The 4 loads of a step
+    // are then 4 consecutive blocks: 4 KiB of contiguous memory per wavefront and step.
     const GlobalBytes Wb = (GlobalBytes)a.W;
     auto row_offsets = [&](int pass, unsigned (&wo)[kRowsPerLane]) {
-        const int tile_row0 = pass * ZR + tile_in_pass * kTileRows + rs * kRowsPerLane;
+        if constexpr (TILED) {
+            const int tile = min(pass * (WAVES / KS) + tile_in_pass, a.tiles - 1);
 #pragma unroll
-        for (int r = 0; r < kRowsPerLane; ++r) {
-            const int row = min(tile_row0 + r, a.V_rows - 1);
-            wo[r] = ((unsigned)row * (unsigned)a.d8 + (unsigned)(s_begin * kStep16 + lk)) * 16u;
+            for (int r = 0; r < kRowsPerLane; ++r)
+                wo[r] = (unsigned)tile * ((unsigned)a.d8 * (kTileRows * 16u)) +
+                        (unsigned)(s_begin * kRowsPerLane + r) * 1024u + (unsigned)lane * 16u;
+        } else {
+            const int tile_row0 = pass * ZR + tile_in_pass * kTileRows + rs * kRowsPerLane;
+#pragma unroll
+            for (int r = 0; r < kRowsPerLane; ++r) {
+                const int row = min(tile_row0 + r, a.V_rows - 1);
+                wo[r] = ((unsigned)row * (unsigned)a.d8 + (unsigned)(s_begin * kStep16 + lk)) * 16u;
+            }
         }
     };
-    constexpr unsigned kStepBytes = kStep16 * 16;
+    constexpr unsigned kStepBytes = TILED ? kRowsPerLane * 1024u : kStep16 * 16;
     constexpr unsigned kGroupBytes = DEPTH * kStepBytes;
 
     // Start of the stream.  Loads return in issue order, so the (small, L2-resident) H is
@@ -194,9 +212,9 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     // stage H (zero padded to whole steps, and to MT rows where the tiles need it)
 #pragma unroll
     for (int m = 0; m < kHRowsMax; ++m)
-        if (m < hrows && tid < hpitch)
+        if (m < hrows && tid < hcols)
             H_lds[m * hpitch + tid] = (tid < a.d8 && m < a.M) ? hpre[m] : zero_u32x4();
-    for (int c = tid + NT; c < hpitch; c += NT)   // columns past the first NT: not held in registers
+    for (int c = tid + NT; c < hcols; c += NT)   // columns past the first NT: not held in registers
         for (int m = 0; m < hrows; ++m) {
             u32x4 v = zero_u32x4();
             if (m < a.M && c < a.d8) v = a.H[(size_t)m * a.d8 + c];
@@ -230,7 +248,18 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
         // 16 rows x 128 elements) against the M rows of H.  `c0` is the index of the step's
         // first 16-byte chunk along d.
         auto compute = [&](const u32x4 (&w)[kRowsPerLane], int c0) {
-            if constexpr (MFMA) {
+            if constexpr (MFMA && TILED) {
+                // the 4 loads of the step are the A operands of its 4 products as they are
+                const int hrow = lk < a.M ? lk : a.M - 1;   // columns >= M are never read back
+                bf16x8_t bf[4];
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk)
+                    bf[kk] = __builtin_bit_cast(bf16x8_t, H_lds[hrow * hpitch + c0 + kk * 4 + rs]);
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk)
+                    accm = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, w[kk]), bf[kk],
+                                                                   accm, 0, 0, 0);
+            } else if constexpr (MFMA) {
                 // Transpose through LDS into MFMA operand order: the loads deliver
                 // (row slot, 16-byte chunk) per lane, the A operand wants (row, 8-element
                 // group).  Only this wavefront touches its staging rows and LDS executes a
@@ -318,10 +347,13 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
             unsigned wr[kRowsPerLane];
             row_offsets(p, wr);
             for (int s = s_pipe_end; s < s_end; ++s) {
-                const int c = min(s * kStep16 + lk, a.d8 - 1) - (s_begin * kStep16 + lk);
+                // byte offset of step s relative to step s_begin (tiled: whole steps only, the
+                // host admits the layout only for d a multiple of 128)
+                const unsigned c = TILED ? (unsigned)(s - s_begin) * kStepBytes
+                                         : (unsigned)(min(s * kStep16 + lk, a.d8 - 1) - (s_begin * kStep16 + lk)) * 16u;
                 u32x4 w[kRowsPerLane];
 #pragma unroll
-                for (int r = 0; r < kRowsPerLane; ++r) w[r] = load_w(Wb, wr[r] + (unsigned)c * 16u);
+                for (int r = 0; r < kRowsPerLane; ++r) w[r] = load_w(Wb, wr[r] + c);
                 compute(w, s * kStep16);
             }
         }
@@ -418,9 +450,9 @@ int bucket_for(int M) {
     return -1;
 }
 
-template <int MT, int WAVES, int DEPTH, bool MFMA>
+template <int MT, int WAVES, int DEPTH, bool MFMA, bool TILED = false>
 fr_status launch_one(const SkinnyArgs &a, int grid, int lds, hipStream_t s) {
-    auto kern = skinny_kernel<MT, WAVES, DEPTH, MFMA>;
+    auto kern = skinny_kernel<MT, WAVES, DEPTH, MFMA, TILED>;
     static bool attr_done = false;   // raising the dynamic LDS limit is idempotent
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -454,6 +486,7 @@ fr_status launch_dot(int MT, const SkinnyArgs &a, int grid, int lds, hipStream_t
 struct Variant {
     int waves, depth;
     bool mfma;
+    bool tiled;
 };
 // Build variants: waves per workgroup, pipeline depth, and whether the products run on
 // the matrix cores or on the packed-bf16 dot instruction of the vector ALUs.  The matrix
@@ -466,8 +499,12 @@ struct Variant {
 //   3  matrix cores, 8 waves, 6 stages
 //   4  vector ALUs, 8 waves, 4 stages (2 stages when more than 10 rows of H: registers)
 //   5  vector ALUs, 8 waves, 3 stages
-constexpr Variant kVariants[] = {{8, 4, true}, {4, 8, true}, {8, 3, true},
-                                 {8, 6, true}, {8, 4, false}, {8, 3, false}};
+//   6  matrix cores, tiled W, 8 waves, 4 stages   (default for the tiled layout)
+//   7  matrix cores, tiled W, 8 waves, 6 stages
+//   8  matrix cores, tiled W, 8 waves, 8 stages
+constexpr Variant kVariants[] = {{8, 4, true, false}, {4, 8, true, false}, {8, 3, true, false},
+                                 {8, 6, true, false}, {8, 4, false, false}, {8, 3, false, false},
+                                 {8, 4, true, true}, {8, 6, true, true}, {8, 8, true, true}};
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 constexpr int kMfmaTile = 16;   // the matrix-core variant is compiled once, for up to 16 rows
 
@@ -475,7 +512,7 @@ int lds_bytes(int M, int d, int k, int variant) {
     const int steps = (d / 8 + kLanesAlongD - 1) / kLanesAlongD;
     const Variant &v = kVariants[variant];
     const int MT = v.mfma ? kMfmaTile : bucket_for(M);
-    return SkinnyLds(MT, v.mfma ? M : MT, v.waves, steps, k, v.mfma).total;
+    return SkinnyLds(MT, v.mfma ? M : MT, v.waves, steps, k, v.mfma, v.tiled).total;
 }
 
 bool variant_fits(int M, int d, int k, int variant) {
@@ -483,7 +520,8 @@ bool variant_fits(int M, int d, int k, int variant) {
 }
 
 // -1 if no build of the skinny kernel can hold this problem's H in LDS
-int default_variant(int M, int d, int k, bool vector_alu) {
+int default_variant(int M, int d, int k, bool vector_alu, bool tiled) {
+    if (tiled) return variant_fits(M, d, k, 6) ? 6 : -1;
     if (vector_alu) return variant_fits(M, d, k, 4) ? 4 : -1;
     if (variant_fits(M, d, k, 0)) return 0;
     if (variant_fits(M, d, k, 1)) return 1;
@@ -493,16 +531,18 @@ int default_variant(int M, int d, int k, bool vector_alu) {
 }  // namespace
 
 bool skinny_fits(int M, int d, int k) {
-    return M <= kSkinnyMaxM && default_variant(M, d, k, false) >= 0;
+    return M <= kSkinnyMaxM && default_variant(M, d, k, false, false) >= 0;
 }
 
 fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hipStream_t s) {
     if (p.M > kSkinnyMaxM) return FR_ERR_UNSUPPORTED;
     const bool vector_alu = t && t->path == 1;
-    int variant = default_variant(p.M, p.d, p.k, vector_alu);
+    if (p.tiled && (vector_alu || p.d % 128 != 0)) return FR_ERR_UNSUPPORTED;
+    int variant = default_variant(p.M, p.d, p.k, vector_alu, p.tiled);
     if (t && t->variant > 0) {
         if (t->variant > kNumVariants) return FR_ERR_INVALID_ARG;
         variant = t->variant - 1;
+        if (kVariants[variant].tiled != p.tiled) return FR_ERR_INVALID_ARG;   // a build reads one layout
         if (!variant_fits(p.M, p.d, p.k, variant)) return FR_ERR_UNSUPPORTED;
     }
     if (variant < 0) return FR_ERR_UNSUPPORTED;
@@ -520,6 +560,7 @@ fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hip
     a.d8 = p.d / 8;
     a.V_rows = p.V_rows;
     a.k = p.k;
+    a.tiles = (p.V_rows + kTileRows - 1) / kTileRows;
     a.steps = (a.d8 + kLanesAlongD - 1) / kLanesAlongD;
 
     // Split d between wavefronts until every compute unit has a workgroup, as far as
@@ -565,6 +606,9 @@ fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hip
         case 3: st = launch_one<kMfmaTile, 8, 6, true>(a, grid, lds, s); break;
         case 4: st = MT > 10 ? launch_dot<8, 2>(MT, a, grid, lds, s) : launch_dot<8, 4>(MT, a, grid, lds, s); break;
         case 5: st = launch_dot<8, 3>(MT, a, grid, lds, s); break;
+        case 6: st = launch_one<kMfmaTile, 8, 4, true, true>(a, grid, lds, s); break;
+        case 7: st = launch_one<kMfmaTile, 8, 6, true, true>(a, grid, lds, s); break;
+        case 8: st = launch_one<kMfmaTile, 8, 8, true, true>(a, grid, lds, s); break;
         default: return FR_ERR_INVALID_ARG;
     }
     if (st != FR_OK) return st;
