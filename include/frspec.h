@@ -87,6 +87,17 @@ size_t fr_workspace_bytes(int64_t M, int64_t d, int64_t V_rows, int32_t k);
 fr_status fr_workspace_init(void *workspace, size_t workspace_bytes, fr_stream stream);
 
 /*
+ * Reads the workspace's sticky time-out word.  The single-launch kernels wait, inside the
+ * launch, for partial results of other workgroups; every such wait is bounded, and a wait that
+ * ever ran out (only possible if workgroups of one launch could not make progress for about a
+ * second, or if the workspace was not prepared) sets the word and lets the call finish with
+ * meaningless outputs.  *timed_out receives 0 or 1.  Synchronous: copies 4 bytes to the host
+ * and waits for everything queued on `stream` before it.  fr_workspace_init clears the word.
+ */
+fr_status fr_workspace_check(const void *workspace, size_t workspace_bytes, int32_t *timed_out,
+                             fr_stream stream);
+
+/*
  * Eq. 4, candidate selection and id translation in one pass over W_sub:
  *   z[m, i]    = sum_j H[m, j] * W_sub[i, j]          bf16 products, fp32 accumulation
  *   logp[m, i] = z[m, i] - log sum_{i' < V_sub} exp(z[m, i'])   (the subset only)

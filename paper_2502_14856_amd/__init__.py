@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     fr_tree_select,
     fr_version,
     fr_workspace_bytes,
+    fr_workspace_check,
     fr_workspace_init,
     lib,
     lib_path,

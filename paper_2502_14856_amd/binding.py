@@ -58,6 +58,7 @@ def lib():
         L.fr_workspace_bytes.argtypes = [i64, i64, i64, i32]
         L.fr_workspace_bytes.restype = sz
         L.fr_workspace_init.argtypes = [vp, sz, vp]
+        L.fr_workspace_check.argtypes = [vp, sz, ctypes.POINTER(ctypes.c_int32), vp]
         L.fr_draft_topk.argtypes = [vp, i64, i64, vp, vp, i64, i32, vp, vp, vp, sz, vp]
         L.fr_draft_topk_tuned.argtypes = [vp, i64, i64, vp, vp, i64, i32, vp, vp, vp, sz, vp,
                                           ctypes.POINTER(Tuning)]
@@ -72,7 +73,7 @@ def lib():
         L.fr_tree_select.argtypes = [vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp]
         L.fr_calib_copy.argtypes = [vp, vp, sz, vp]
         L.fr_calib_read.argtypes = [vp, sz, vp, vp]
-        for name in ("fr_build_subset", "fr_workspace_init", "fr_draft_topk", "fr_draft_topk_tuned",
+        for name in ("fr_build_subset", "fr_workspace_init", "fr_workspace_check", "fr_draft_topk", "fr_draft_topk_tuned",
                      "fr_full_topk", "fr_draft_logits", "fr_beam_expand", "fr_tree_select", "fr_build_subset_tiled",
                      "fr_draft_topk_tiled", "fr_calib_copy",
                      "fr_calib_read"):
@@ -121,6 +122,14 @@ def fr_workspace_bytes(M: int, d: int, V_rows: int, k: int) -> int:
 def fr_workspace_init(workspace, stream=None) -> None:
     _check(lib().fr_workspace_init(_ptr(workspace), workspace.numel() * workspace.element_size(),
                                    _stream(stream)), "fr_workspace_init")
+
+
+def fr_workspace_check(workspace, stream=None) -> bool:
+    """True if a bounded in-kernel wait ever ran out on this workspace (synchronises)."""
+    flag = ctypes.c_int32(0)
+    _check(lib().fr_workspace_check(_ptr(workspace), workspace.numel() * workspace.element_size(),
+                                    ctypes.byref(flag), _stream(stream)), "fr_workspace_check")
+    return bool(flag.value)
 
 
 def new_workspace(M: int, d: int, V_rows: int, k: int, device="cuda", stream=None):

@@ -192,6 +192,23 @@ fr_status fr_workspace_init(void *workspace, size_t workspace_bytes, fr_stream s
                            mail / 4, 0xFFFFFFFFu, static_cast<hipStream_t>(stream));
 }
 
+fr_status fr_workspace_check(const void *workspace, size_t workspace_bytes, int32_t *timed_out,
+                             fr_stream stream) {
+    if (!workspace || !timed_out) return FR_ERR_INVALID_ARG;
+    if (!aligned16(workspace)) return FR_ERR_ALIGNMENT;
+    if (workspace_bytes < kWorkspaceHeaderBytes) return FR_ERR_WORKSPACE;
+    unsigned word = 0;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (hipMemcpyAsync(&word, static_cast<const unsigned *>(workspace) + 1, sizeof word, hipMemcpyDeviceToHost, s) !=
+            hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess) {
+        (void)hipGetLastError();
+        return FR_ERR_HIP;
+    }
+    *timed_out = word != 0;
+    return FR_OK;
+}
+
 fr_status fr_draft_topk(const void *H, int64_t M, int64_t d, const void *W_sub,
                         const int32_t *idx_map, int64_t V_sub, int32_t k, int32_t *token_ids,
                         float *logp, void *workspace, size_t workspace_bytes, fr_stream stream) {

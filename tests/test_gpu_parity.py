@@ -268,3 +268,35 @@ def test_workspace_reuse_with_changing_inputs_sees_no_stale_partials():
     for h, (ids_g, lp_g) in zip(Hs, outs):
         ids_o, lp_o, z_o = oracle.draft_topk(h, W_o, idx_o, k, want_logits=True)
         check_topk_against_oracle(ids_g.cpu().numpy(), lp_g.cpu().numpy(), z_o, idx_o, ids_o, lp_o)
+
+
+def test_one_workspace_across_changing_shapes_leaves_the_mailbox_empty():
+    # The skinny kernel's single-launch merge passes results through self-validating records
+    # that must all be empty again when a call ends, whatever M, k and the number of
+    # workgroups were; a record left behind would be taken for a result by a later call.
+    _say("workspace reuse, changing shapes")
+    W, _, r = _case(9000, 256, 16, 21)
+    ws = fr.new_workspace(16, 256, 9000, 16)
+    W_d, r_d = to_dev_bf16(W), to_dev_i32(r)
+    g = np.random.default_rng(22)
+    shapes = [(10, 10, 4096, {}), (3, 16, 9000, {}), (16, 1, 100, {}), (10, 10, 4096, dict(grid=5)),
+              (1, 7, 2048, dict(ksplit=2)), (12, 12, 6000, {}), (10, 10, 4096, dict(path=1)), (16, 16, 9000, {})]
+    for rep in range(2):
+        for M, k, V_sub, knobs in shapes:
+            H = f32_to_bf16_bits(g.standard_normal((M, 256)).astype(np.float32))
+            W_o, idx_o = oracle.build_subset(W, r, V_sub)
+            ids_o, lp_o, z_o = oracle.draft_topk(H, W_o, idx_o, k, want_logits=True)
+            W_g, idx_g = fr.fr_build_subset(W_d, r_d, V_sub)
+            t = None
+            if knobs:
+                t = Tuning()
+                for key, val in knobs.items():
+                    setattr(t, key, val)
+            ids_g, lp_g = fr.fr_draft_topk(to_dev_bf16(H), W_g, idx_g, k, ws, tuning=t)
+            _sync()
+            check_topk_against_oracle(ids_g.cpu().numpy(), lp_g.cpu().numpy(), z_o, idx_o, ids_o, lp_o)
+            mail = ws[512:512 + (16 * 16 + 16) * 512 * 8].cpu().numpy()
+            assert (mail == 0xFF).all(), (M, k, V_sub, knobs)
+            head = ws[:512].cpu().numpy().view(np.uint32)
+            assert head[1] == 0      # no wait ever timed out
+    assert fr.fr_workspace_check(ws) is False
