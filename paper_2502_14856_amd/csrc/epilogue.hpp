@@ -346,25 +346,26 @@ struct FoldSink {
  * `active` false if that row does not exist) and holds C = ZR_MAX / 32 consecutive local
  * vocabulary rows, plus entry l32 of the row's running list when WITH_RUN.  A group is
  * the pair of lanes (l32, l32 ^ 16).
- *   z_lds   logits of the pass, row m at z_lds + m * ZR (+ q * z_slice_stride for slice q
- *           of a split d); the logit is the sum of the slices in slice order
+ *   z_lds   logits of the pass, row m at z_lds + (m - m_base) * z_row_stride (+ q *
+ *           z_slice_stride for slice q of a split d); the logit is the sum of the slices in
+ *           slice order
  * Returns false, having written nothing, when more than 32 candidates of a row survive
  * the bound (heavily tied values, or fewer than k populated groups): the caller then
  * takes the general path for both rows.
  */
 template <int ZR_MAX, bool WITH_RUN>
-__device__ __forceinline__ bool fold_pair_fast(const float *z_lds, int ZR, int KS, int z_slice_stride,
-                                               const int *ids_pass, int n_valid, int k, int m, bool active,
-                                               const FoldSink &out, SelectScratch *sc) {
+__device__ __forceinline__ bool fold_pair_fast(const float *z_lds, int z_row_stride, int m_base, int KS,
+                                               int z_slice_stride, const int *ids_pass, int n_valid, int k, int m,
+                                               bool active, const FoldSink &out, SelectScratch *sc) {
     constexpr int C = ZR_MAX / 32;
     constexpr int CPL = C + (WITH_RUN ? 1 : 0);
     const int lane = lane_id(), h = lane >> 5, l32 = lane & 31;
-    const int mm = active ? m : 0;
+    const int mm = active ? m : m_base;
 
     float z[C];
 #pragma unroll
     for (int c = 0; c < C; ++c) z[c] = 0.0f;
-    const float *zp = z_lds + mm * ZR + l32 * C;
+    const float *zp = z_lds + (mm - m_base) * z_row_stride + l32 * C;
     for (int q = 0; q < KS; ++q) {
         float t[C];
         lds_words<C, float, fvec4, fvec2>(zp + q * z_slice_stride, t);
@@ -471,29 +472,30 @@ __device__ __noinline__ void fold_row_general(FoldRow row, int KS, int z_slice_s
 }
 
 /*
- * Folds one pass into the running state of all M rows of H, or, on the workgroup's last
- * pass, writes the result out (see FoldSink).  Wavefront w of `waves` takes rows w and
- * w + waves (then + 2 * waves, ...), two at a time in its two halves while k <= 16.
+ * Folds one pass into the running state of rows m_base <= m < m_end of H, or, on the
+ * workgroup's last pass, writes the result out (see FoldSink).  Wavefront w of `waves` takes
+ * rows m_base + w and m_base + w + waves (then + 2 * waves, ...), two at a time in its two
+ * halves while k <= 16.
  */
 template <int ZR_MAX, bool WITH_RUN, typename RowOf>
-__device__ __forceinline__ void fold_pass(const float *z_lds, int ZR, int KS, int z_slice_stride,
-                                          const int *ids_pass, int n_valid, int k, int M, int wave, int waves,
-                                          RowOf row_of, const FoldSink &out, SelectScratch *sc) {
+__device__ __forceinline__ void fold_pass(const float *z_lds, int z_row_stride, int KS, int z_slice_stride,
+                                          const int *ids_pass, int n_valid, int k, int m_base, int m_end, int wave,
+                                          int waves, RowOf row_of, const FoldSink &out, SelectScratch *sc) {
     if (k <= kSmallKMax) {
-        for (int mb = 0; mb < M; mb += 2 * waves) {
+        for (int mb = m_base; mb < m_end; mb += 2 * waves) {
             const int m_lo = mb + wave, m_hi = mb + wave + waves;
-            if (m_lo >= M) break;
+            if (m_lo >= m_end) break;
             const int m = (lane_id() >> 5) ? m_hi : m_lo;
-            if (fold_pair_fast<ZR_MAX, WITH_RUN>(z_lds, ZR, KS, z_slice_stride, ids_pass, n_valid, k, m, m < M,
-                                                 out, sc))
+            if (fold_pair_fast<ZR_MAX, WITH_RUN>(z_lds, z_row_stride, m_base, KS, z_slice_stride, ids_pass, n_valid,
+                                                 k, m, m < m_end, out, sc))
                 continue;
             fold_row_general<ZR_MAX, WITH_RUN>(row_of(m_lo), KS, z_slice_stride, ids_pass, n_valid, k, sc, out, m_lo);
-            if (m_hi < M)
+            if (m_hi < m_end)
                 fold_row_general<ZR_MAX, WITH_RUN>(row_of(m_hi), KS, z_slice_stride, ids_pass, n_valid, k, sc, out,
                                                    m_hi);
         }
     } else {
-        for (int m = wave; m < M; m += waves)
+        for (int m = m_base + wave; m < m_end; m += waves)
             fold_row_general<ZR_MAX, WITH_RUN>(row_of(m), KS, z_slice_stride, ids_pass, n_valid, k, sc, out, m);
     }
 }

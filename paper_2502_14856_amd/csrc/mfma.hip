@@ -290,12 +290,14 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
                     return FoldRow{z_stage + (m - mt * 16) * (kZR + kZPad), run_ms + 2 * m,
                                    run_val + m * a.k, run_id + m * a.k};
                 };
+                // the running state stays in LDS; it is written out once, after the last pass
+                const FoldSink out{FoldTo::kLds, Partials{}, Mailbox{}, 0, run_ms, run_val, run_id};
                 if (p == (int)blockIdx.x)
-                    block_fold_all<kZR, false>(mt * 16 + wave, WAVES, m_end, row_of, 1, 0, ids_lds, n_valid,
-                                               a.k, &s_select[wave]);
+                    fold_pass<kZR, false>(z_stage, kZR + kZPad, 1, 0, ids_lds, n_valid, a.k, mt * 16, m_end, wave,
+                                          WAVES, row_of, out, &s_select[wave]);
                 else
-                    block_fold_all<kZR, true>(mt * 16 + wave, WAVES, m_end, row_of, 1, 0, ids_lds, n_valid,
-                                              a.k, &s_select[wave]);
+                    fold_pass<kZR, true>(z_stage, kZR + kZPad, 1, 0, ids_lds, n_valid, a.k, mt * 16, m_end, wave,
+                                         WAVES, row_of, out, &s_select[wave]);
             }
         }
     }

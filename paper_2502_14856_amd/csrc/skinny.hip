@@ -401,11 +401,11 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
             const FoldSink out{!last ? FoldTo::kLds : (mailbox ? FoldTo::kMailbox : FoldTo::kPartials),
                                part, a.mail, (int)blockIdx.x, run_ms, run_val, run_id};
             if (p == first_pass)
-                fold_pass<ZR_MAX, false>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, a.M, wave, WAVES, row_of, out,
-                                         &s_select[wave]);
+                fold_pass<ZR_MAX, false>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, 0, a.M, wave, WAVES, row_of,
+                                         out, &s_select[wave]);
             else
-                fold_pass<ZR_MAX, true>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, a.M, wave, WAVES, row_of, out,
-                                        &s_select[wave]);
+                fold_pass<ZR_MAX, true>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, 0, a.M, wave, WAVES, row_of,
+                                        out, &s_select[wave]);
         }
         if (p + G < a.passes) __syncthreads();
     }
