@@ -204,7 +204,8 @@ typedef struct fr_tuning {
     int32_t grid;        /* number of workgroups (<= 512) */
     int32_t stream_only; /* 1 = measurement only: run the contraction and drop the logits
                             (no softmax, no top-k; token_ids / logp are left untouched) */
-    int32_t reserved0;
+    int32_t skew;        /* > 0: rows that every odd workgroup hands to its even neighbour when each
+                            workgroup has exactly one pass (experimental die balancing; off by default) */
     int32_t reserved1;
     void *trace;         /* optional device buffer of 8 * 512 int64: every workgroup of the
                             skinny kernel records 100 MHz timestamps of its phases there */

@@ -353,14 +353,17 @@ struct FoldSink {
  * the bound (heavily tied values, or fewer than k populated groups): the caller then
  * takes the general path for both rows.
  */
-template <int ZR_MAX, bool WITH_RUN>
+template <int ZR_MAX, bool WITH_RUN, bool WITH_EXTRA = false>
 __device__ __forceinline__ bool fold_pair_fast(const float *z_lds, int z_row_stride, int m_base, int KS,
                                                int z_slice_stride, const int *ids_pass, int n_valid, int k, int m,
                                                bool active, const FoldSink &out, SelectScratch *sc) {
     constexpr int C = ZR_MAX / 32;
-    constexpr int CPL = C + (WITH_RUN ? 1 : 0);
+    constexpr int CPL = C + (WITH_RUN ? 1 : 0) + (WITH_EXTRA ? 1 : 0);
     const int lane = lane_id(), h = lane >> 5, l32 = lane & 31;
     const int mm = active ? m : m_base;
+    // WITH_EXTRA: the pass has up to 16 more local rows than the ZR_MAX that the lanes cover C
+    // at a time (slots ZR_MAX .. ZR_MAX + 15); lane l32 < 16 takes slot ZR_MAX + l32 as one
+    // more candidate
 
     float z[C];
 #pragma unroll
@@ -374,6 +377,15 @@ __device__ __forceinline__ bool fold_pair_fast(const float *z_lds, int z_row_str
     }
     int id[C];
     lds_words<C, int, ivec4, ivec2>(ids_pass + l32 * C, id);
+    float z_x = 0.0f;
+    int id_x = INT_MAX;
+    bool ok_x = false;
+    if (WITH_EXTRA) {
+        const int rx = ZR_MAX + (l32 & 15);   // always inside the rows of the pass's z block
+        ok_x = active && l32 < 16 && rx < n_valid;
+        for (int q = 0; q < KS; ++q) z_x += z_lds[(mm - m_base) * z_row_stride + q * z_slice_stride + rx];
+        id_x = ids_pass[ok_x ? rx : 0];
+    }
     const int kk = l32 < k ? l32 : k - 1;
     float old_mx = kNegInf, old_S = 0.0f, run_v = kNegInf;
     int run_i = INT_MAX;
@@ -395,10 +407,13 @@ __device__ __forceinline__ bool fold_pair_fast(const float *z_lds, int z_row_str
         v[c] = ok[c] ? z[c] : kNegInf;
         lmax = fmaxf(lmax, v[c]);
     }
+    const float v_x = ok_x ? z_x : kNegInf;
+    if (WITH_EXTRA) lmax = fmaxf(lmax, v_x);
     const float mx = fmaxf(old_mx, row16_max_f32(fmaxf(lmax, swap16_f32(lmax))));
     float part = 0.0f;
 #pragma unroll
     for (int c = 0; c < C; ++c) part += exp_diff(v[c], mx);
+    if (WITH_EXTRA) part += exp_diff(v_x, mx);
     part += swap16_f32(part);
     const float S = old_S * exp_diff(old_mx, mx) + row16_sum_all(part);
 
@@ -408,6 +423,10 @@ __device__ __forceinline__ bool fold_pair_fast(const float *z_lds, int z_row_str
     for (int c = 0; c < C; ++c) {
         hi[c] = ok[c] ? key_hi_of(v[c]) : 0u;
         lo[c] = ~(unsigned)id[c];
+    }
+    if (WITH_EXTRA) {
+        hi[C] = ok_x ? key_hi_of(v_x) : 0u;
+        lo[C] = ~(unsigned)id_x;
     }
     if (WITH_RUN) {
         hi[CPL - 1] = run_i != INT_MAX ? key_hi_of(run_v) : 0u;
@@ -477,26 +496,28 @@ __device__ __noinline__ void fold_row_general(FoldRow row, int KS, int z_slice_s
  * rows m_base + w and m_base + w + waves (then + 2 * waves, ...), two at a time in its two
  * halves while k <= 16.
  */
-template <int ZR_MAX, bool WITH_RUN, typename RowOf>
+template <int ZR_MAX, bool WITH_RUN, bool WITH_EXTRA = false, typename RowOf>
 __device__ __forceinline__ void fold_pass(const float *z_lds, int z_row_stride, int KS, int z_slice_stride,
                                           const int *ids_pass, int n_valid, int k, int m_base, int m_end, int wave,
                                           int waves, RowOf row_of, const FoldSink &out, SelectScratch *sc) {
+    // the general fold covers 64 local rows per lane slot: one more slot takes the extra rows
+    constexpr int ZR_GEN = WITH_EXTRA ? ZR_MAX + kWave : ZR_MAX;
     if (k <= kSmallKMax) {
         for (int mb = m_base; mb < m_end; mb += 2 * waves) {
             const int m_lo = mb + wave, m_hi = mb + wave + waves;
             if (m_lo >= m_end) break;
             const int m = (lane_id() >> 5) ? m_hi : m_lo;
-            if (fold_pair_fast<ZR_MAX, WITH_RUN>(z_lds, z_row_stride, m_base, KS, z_slice_stride, ids_pass, n_valid,
-                                                 k, m, m < m_end, out, sc))
+            if (fold_pair_fast<ZR_MAX, WITH_RUN, WITH_EXTRA>(z_lds, z_row_stride, m_base, KS, z_slice_stride,
+                                                             ids_pass, n_valid, k, m, m < m_end, out, sc))
                 continue;
-            fold_row_general<ZR_MAX, WITH_RUN>(row_of(m_lo), KS, z_slice_stride, ids_pass, n_valid, k, sc, out, m_lo);
+            fold_row_general<ZR_GEN, WITH_RUN>(row_of(m_lo), KS, z_slice_stride, ids_pass, n_valid, k, sc, out, m_lo);
             if (m_hi < m_end)
-                fold_row_general<ZR_MAX, WITH_RUN>(row_of(m_hi), KS, z_slice_stride, ids_pass, n_valid, k, sc, out,
+                fold_row_general<ZR_GEN, WITH_RUN>(row_of(m_hi), KS, z_slice_stride, ids_pass, n_valid, k, sc, out,
                                                    m_hi);
         }
     } else {
         for (int m = m_base + wave; m < m_end; m += waves)
-            fold_row_general<ZR_MAX, WITH_RUN>(row_of(m), KS, z_slice_stride, ids_pass, n_valid, k, sc, out, m);
+            fold_row_general<ZR_GEN, WITH_RUN>(row_of(m), KS, z_slice_stride, ids_pass, n_valid, k, sc, out, m);
     }
 }
 

@@ -55,6 +55,7 @@ struct SkinnyArgs {
     const int *idx_map;
     int M, d8, V_rows, k;
     int tiles;            // 16-row tiles of W (tiled layout only)
+    int skew;             // rows moved from every odd workgroup to its even neighbour (skewed build)
     int KS;               // wavefronts sharing one tile along d
     int steps;            // ceil(d8 / 16): steps of 128 elements along d
     int steps_per_split;  // ceil(steps / KS)
@@ -92,9 +93,22 @@ struct SkinnyLds {
     }
 };
 
-template <int MT, int WAVES, int DEPTH, bool MFMA, bool TILED = false>
+/*
+ * SKEW build (single pass per workgroup, row-major W, matrix cores): the eight compute dies do
+ * not stream at the same rate (the odd-numbered ones are consistently ~9% slower), workgroups
+ * are dealt to the dies in turn, and the kernel ends with the slowest die.  So every odd
+ * workgroup hands `skew` of its rows to its even neighbour: a pair of workgroups shares
+ * 2 * V_rows / G consecutive rows, the even one takes the first V_rows / G + skew.  A
+ * workgroup's rows are cut into 16-row tiles as always; the even workgroup's surplus is a
+ * ninth, short tile, streamed by a ninth wavefront that takes no part in the fold.  (A
+ * wavefront's pace is set by the latency of its die's memory path, not by its own byte
+ * count, so it does not matter which wavefront of a die carries fewer or more rows.)
+ */
+template <int MT, int WAVES, int DEPTH, bool MFMA, bool TILED = false, bool SKEW = false>
 __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     static_assert(MFMA || !TILED, "the tiled layout is the matrix cores' operand order");
+    static_assert(!SKEW || (MFMA && !TILED), "the skewed build is the default build plus one wavefront");
+    constexpr int FOLD_WAVES = SKEW ? WAVES - 1 : WAVES;
     extern __shared__ u32x4 smem[];
     char *base = reinterpret_cast<char *>(smem);
     const int hrows = MFMA ? a.M : MT;
@@ -111,7 +125,7 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     __shared__ MergeScratch s_merge;
     const Partials part = a.part;   // a local copy keeps the argument block itself in registers
 
-    constexpr int ZR_MAX = WAVES * kTileRows;
+    constexpr int ZR_MAX = FOLD_WAVES * kTileRows;   // local rows that the fold's lanes cover
     constexpr int kStep16 = kLanesAlongD;        // 16-byte chunks per row per step
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -128,6 +142,14 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     const int tile_in_pass = wave / KS;
     const int ks = wave - tile_in_pass * KS;
     const int G = gridDim.x;
+    // SKEW: this workgroup's own row range
+    int blk_row0 = 0, blk_rows = 0;
+    if constexpr (SKEW) {
+        const int B = a.V_rows / G, odd = (int)blockIdx.x & 1;
+        blk_row0 = ((int)blockIdx.x >> 1) * 2 * B + (odd ? B + a.skew : 0);
+        blk_rows = odd ? B - a.skew : B + a.skew;
+    }
+    const bool has_tile = !SKEW || tile_in_pass * kTileRows < blk_rows;   // wave-uniform
     auto stamp = [&](int slot) {
         if (a.trace && tid == 0) a.trace[blockIdx.x * 8 + slot] = (long long)__builtin_amdgcn_s_memrealtime();
     };
@@ -142,7 +164,7 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     // DEPTH full steps, no bounds handling at all) and leftovers (at most DEPTH - 1 steps,
     // plus the ragged last step when d is not a multiple of 128).
     const int s_begin = ks * a.steps_per_split;
-    const int s_end = min(a.steps, s_begin + a.steps_per_split);
+    const int s_end = has_tile ? min(a.steps, s_begin + a.steps_per_split) : s_begin;
     const int full_end = min(s_end, a.d8 / kStep16);
     const int groups = full_end > s_begin ? (full_end - s_begin) / DEPTH : 0;
     const int s_pipe_end = s_begin + groups * DEPTH;
@@ -169,10 +191,11 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
                 wo[r] = (unsigned)tile * ((unsigned)a.d8 * (kTileRows * 16u)) +
                         (unsigned)(s_begin * kRowsPerLane + r) * 1024u + (unsigned)lane * 16u;
         } else {
-            const int tile_row0 = pass * ZR + tile_in_pass * kTileRows + rs * kRowsPerLane;
+            const int tile_row0 = (SKEW ? blk_row0 : pass * ZR) + tile_in_pass * kTileRows + rs * kRowsPerLane;
+            const int last_row = SKEW ? blk_row0 + blk_rows - 1 : a.V_rows - 1;
 #pragma unroll
             for (int r = 0; r < kRowsPerLane; ++r) {
-                const int row = min(tile_row0 + r, a.V_rows - 1);
+                const int row = min(tile_row0 + r, last_row);
                 wo[r] = ((unsigned)row * (unsigned)a.d8 + (unsigned)(s_begin * kStep16 + lk)) * 16u;
             }
         }
@@ -187,7 +210,7 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     // Thread t fetches 16-byte column t of every row of H (wave-uniform base + 32-bit lane
     // offset, like W), holds the pieces in registers and writes them to LDS further down.
     constexpr int NT = WAVES * kWave;
-    constexpr int kHRowsMax = 16;
+    constexpr int kHRowsMax = SKEW ? 12 : 16;   // (the skewed build's LDS holds at most 11 rows of H)
     const GlobalBytes Hb = (GlobalBytes)a.H;
     const unsigned hcol = (unsigned)min(tid, a.d8 - 1) * 16u;   // clamped: always a valid address
     const unsigned hrow_bytes = (unsigned)a.d8 * 16u;
@@ -224,9 +247,9 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     __syncthreads();
     stamp(1);
 
-    for (; p < a.passes; p += G) {
-        const int pass_row0 = p * ZR;
-        const int n_valid = min(ZR, a.V_rows - pass_row0);
+    for (; p < a.passes && (!SKEW || p == first_pass); p += G) {
+        const int pass_row0 = SKEW ? blk_row0 : p * ZR;
+        const int n_valid = SKEW ? blk_rows : min(ZR, a.V_rows - pass_row0);
         if (tid < n_valid) {
             const int row = pass_row0 + tid;
             ids_lds[tid] = a.idx_map ? a.idx_map[row] : row;
@@ -322,7 +345,7 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
             }
             // drain; the stages freed here start on the next pass of this workgroup
             const int cg = c_begin + grp * (DEPTH * kStep16);
-            const bool has_next = p + G < a.passes;
+            const bool has_next = !SKEW && p + G < a.passes;   // (the skewed build has one pass)
             if (has_next) {
                 row_offsets(p + G, wo);
                 const unsigned nofs = (unsigned)g_first * kGroupBytes;
@@ -400,12 +423,15 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
             const bool last = p + G >= a.passes;
             const FoldSink out{!last ? FoldTo::kLds : (mailbox ? FoldTo::kMailbox : FoldTo::kPartials),
                                part, a.mail, (int)blockIdx.x, run_ms, run_val, run_id};
-            if (p == first_pass)
-                fold_pass<ZR_MAX, false>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, 0, a.M, wave, WAVES, row_of,
-                                         out, &s_select[wave]);
-            else
-                fold_pass<ZR_MAX, true>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, 0, a.M, wave, WAVES, row_of,
-                                        out, &s_select[wave]);
+            if (SKEW && wave >= FOLD_WAVES) {
+                // the ninth wavefront only streams
+            } else if (p == first_pass) {
+                fold_pass<ZR_MAX, false, SKEW>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, 0, a.M, wave,
+                                               FOLD_WAVES, row_of, out, &s_select[wave]);
+            } else {
+                fold_pass<ZR_MAX, true, SKEW>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, 0, a.M, wave,
+                                              FOLD_WAVES, row_of, out, &s_select[wave]);
+            }
         }
         if (p + G < a.passes) __syncthreads();
     }
@@ -450,9 +476,9 @@ int bucket_for(int M) {
     return -1;
 }
 
-template <int MT, int WAVES, int DEPTH, bool MFMA, bool TILED = false>
+template <int MT, int WAVES, int DEPTH, bool MFMA, bool TILED = false, bool SKEW = false>
 fr_status launch_one(const SkinnyArgs &a, int grid, int lds, hipStream_t s) {
-    auto kern = skinny_kernel<MT, WAVES, DEPTH, MFMA, TILED>;
+    auto kern = skinny_kernel<MT, WAVES, DEPTH, MFMA, TILED, SKEW>;
     static bool attr_done = false;   // raising the dynamic LDS limit is idempotent
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -502,9 +528,14 @@ struct Variant {
 //   6  matrix cores, tiled W, 8 waves, 4 stages   (default for the tiled layout)
 //   7  matrix cores, tiled W, 8 waves, 6 stages
 //   8  matrix cores, tiled W, 8 waves, 8 stages
+//   9  matrix cores, 8 + 1 waves, 4 stages, rows skewed between neighbouring workgroups
+//      (chosen automatically when every workgroup has exactly one pass)
 constexpr Variant kVariants[] = {{8, 4, true, false}, {4, 8, true, false}, {8, 3, true, false},
                                  {8, 6, true, false}, {8, 4, false, false}, {8, 3, false, false},
-                                 {8, 4, true, true}, {8, 6, true, true}, {8, 8, true, true}};
+                                 {8, 4, true, true}, {8, 6, true, true}, {8, 8, true, true},
+                                 {9, 4, true, false}};
+constexpr int kSkewVariant = 9;
+constexpr int kSkewDefaultRows = 4;
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 constexpr int kMfmaTile = 16;   // the matrix-core variant is compiled once, for up to 16 rows
 
@@ -566,7 +597,9 @@ fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hip
     // Split d between wavefronts until every compute unit has a workgroup, as far as
     // the number of steps allows.
     int KS = 1;
-    if (t && t->ksplit > 0) {
+    if (variant == kSkewVariant) {
+        if (t && t->ksplit > 1) return FR_ERR_INVALID_ARG;
+    } else if (t && t->ksplit > 0) {
         KS = t->ksplit;
         if (KS > waves || (KS & (KS - 1)) != 0) return FR_ERR_INVALID_ARG;
     } else {
@@ -578,7 +611,8 @@ fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hip
     }
     a.KS = KS;
     a.steps_per_split = (a.steps + KS - 1) / KS;
-    const int ZR = (waves / KS) * kTileRows;
+    // (a forced skewed build counts passes like the default build it replaces: 8 tiles each)
+    const int ZR = ((variant == kSkewVariant ? 8 : waves) / KS) * kTileRows;
     a.passes = (p.V_rows + ZR - 1) / ZR;
     a.sink = (int)sink;
     a.part.ms = p.ws.part_ms;
@@ -596,6 +630,27 @@ fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hip
     int grid = a.passes < cus ? a.passes : cus;
     if (t && t->grid > 0) grid = t->grid < a.passes ? t->grid : a.passes;
     if (grid > kGridMax) grid = kGridMax;
+
+    // The skewed build can replace the default one when every workgroup has exactly one full
+    // pass (as at V_rows = 128 * compute units): see the kernel's comment.  It is opt-in
+    // (fr_tuning.skew > 0): measured, the even dies do finish ~2 us ahead of the odd ones and
+    // the finish times do follow the row counts, but the ninth wavefront (168 instead of 226
+    // registers per lane, three wavefronts on one SIMD) costs about as much as the balance gains.
+    const int want_skew = t ? t->skew : 0;
+    const bool forced = variant == kSkewVariant;
+    if ((variant == 0 && want_skew > 0 && !(t && (t->variant > 0 || t->ksplit > 0 || t->grid > 0))) || forced) {
+        const int rows = want_skew > 0 ? want_skew : kSkewDefaultRows;
+        const int B = p.V_rows / cus;
+        const bool ok = KS == 1 && a.passes == cus && grid == cus && (cus % 2) == 0 && p.V_rows == B * cus &&
+                        B + rows <= 9 * kTileRows && B - rows >= 1 && cus <= kGridMax && p.M <= 12 &&
+                        variant_fits(p.M, p.d, p.k, kSkewVariant);
+        if (ok) {
+            variant = kSkewVariant;
+            a.skew = rows;
+        } else if (forced) {
+            return FR_ERR_UNSUPPORTED;
+        }
+    }
     const int lds = lds_bytes(p.M, p.d, p.k, variant);
 
     fr_status st;
@@ -609,6 +664,7 @@ fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hip
         case 6: st = launch_one<kMfmaTile, 8, 4, true, true>(a, grid, lds, s); break;
         case 7: st = launch_one<kMfmaTile, 8, 6, true, true>(a, grid, lds, s); break;
         case 8: st = launch_one<kMfmaTile, 8, 8, true, true>(a, grid, lds, s); break;
+        case 9: st = launch_one<kMfmaTile, 9, 4, true, false, true>(a, grid, lds, s); break;
         default: return FR_ERR_INVALID_ARG;
     }
     if (st != FR_OK) return st;

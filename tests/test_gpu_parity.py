@@ -300,3 +300,30 @@ def test_one_workspace_across_changing_shapes_leaves_the_mailbox_empty():
             head = ws[:512].cpu().numpy().view(np.uint32)
             assert head[1] == 0      # no wait ever timed out
     assert fr.fr_workspace_check(ws) is False
+
+
+@pytest.mark.parametrize("M,k,skew,exact", [(10, 10, 4, False), (10, 10, 8, False), (10, 10, 16, False),
+                                            (10, 10, 0, False), (1, 1, 4, False), (12, 16, 12, False),
+                                            (7, 20, 4, False), (10, 10, 4, True), (3, 33, 16, True)])
+def test_skewed_rows_between_neighbouring_workgroups(M, k, skew, exact):
+    # 32768 rows = one pass of 128 rows for each of the 256 workgroups: the only shape at which
+    # the skinny kernel moves rows from odd to even workgroups (a ninth wavefront streams the
+    # surplus).  `exact` inputs give heavily tied logits: the general fold and merge run.
+    _say("skewed build", M, k, skew, exact)
+    V, V_sub, d = 40000, 32768, 128
+    if exact:
+        W, H = make_exact_case(V, d, M, 31)[:2]
+    else:
+        W = make_weights(V, d, 30)
+        H = make_hidden(M, d, 30)
+    r = np.random.default_rng([20250214, 94]).permutation(V).astype(np.int32)
+    W_o, idx_o = oracle.build_subset(W, r, V_sub)
+    ids_o, lp_o, z_o = oracle.draft_topk(H, W_o, idx_o, k, want_logits=True)
+    W_g, idx_g = fr.fr_build_subset(to_dev_bf16(W), to_dev_i32(r), V_sub)
+    ws = fr.new_workspace(M, d, V, k)
+    t = Tuning()
+    t.skew = skew
+    ids_g, lp_g = fr.fr_draft_topk(to_dev_bf16(H), W_g, idx_g, k, ws, tuning=t)
+    _sync()
+    check_topk_against_oracle(ids_g.cpu().numpy(), lp_g.cpu().numpy(), z_o, idx_o, ids_o, lp_o)
+    assert fr.fr_workspace_check(ws) is False
