@@ -219,6 +219,20 @@ fr_status fr_draft_topk_tuned(const void *H, int64_t M, int64_t d,
                               const fr_tuning *tuning);
 
 /*
+ * fr_draft_topk for hidden states that sit in several blocks of memory (several draft heads
+ * evaluated against one W_sub, as when the method is applied to Medusa-style heads, Section
+ * 4.5): block b holds rows_per_block rows, bf16 [rows_per_block, d] row-major; row
+ * m of the combined problem is row m % rows_per_block of block m / rows_per_block; outputs
+ * are [n_blocks * rows_per_block, k].  H_blocks is a HOST array of n_blocks (<= 16) device
+ * pointers, read during the call only.  Up to 16 rows in total run as one launch; beyond,
+ * one launch per block.  Everything else as fr_draft_topk.
+ */
+fr_status fr_draft_topk_multi(const void *const *H_blocks, int32_t n_blocks, int64_t rows_per_block,
+                              int64_t d, const void *W_sub, const int32_t *idx_map, int64_t V_sub,
+                              int32_t k, int32_t *token_ids, float *logp, void *workspace,
+                              size_t workspace_bytes, fr_stream stream);
+
+/*
  * The same subset and the same head with W_sub in a private tiled layout (Eq. 3 fixes the
  * matrix, not how it is stored; the gather rewrites W once anyway).  A tile is 16
  * consecutive rows of W_sub; inside a tile, the 16-byte chunk holding row i (0..15),

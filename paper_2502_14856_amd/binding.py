@@ -64,6 +64,8 @@ def lib():
                                           ctypes.POINTER(Tuning)]
         L.fr_full_topk.argtypes = [vp, i64, i64, vp, i64, i32, vp, vp, vp, sz, vp]
         L.fr_draft_logits.argtypes = [vp, i64, i64, vp, i64, vp, vp]
+        L.fr_draft_topk_multi.argtypes = [ctypes.POINTER(ctypes.c_void_p), i32, i64, i64, vp, vp, i64, i32, vp, vp,
+                                          vp, sz, vp]
         L.fr_tiled_bytes.argtypes = [i64, i64]
         L.fr_tiled_bytes.restype = sz
         L.fr_build_subset_tiled.argtypes = [vp, i64, i64, vp, i64, vp, vp, vp, vp]
@@ -74,7 +76,7 @@ def lib():
         L.fr_calib_copy.argtypes = [vp, vp, sz, vp]
         L.fr_calib_read.argtypes = [vp, sz, vp, vp]
         for name in ("fr_build_subset", "fr_workspace_init", "fr_workspace_check", "fr_draft_topk", "fr_draft_topk_tuned",
-                     "fr_full_topk", "fr_draft_logits", "fr_beam_expand", "fr_tree_select", "fr_build_subset_tiled",
+                     "fr_full_topk", "fr_draft_logits", "fr_beam_expand", "fr_tree_select", "fr_draft_topk_multi", "fr_build_subset_tiled",
                      "fr_draft_topk_tiled", "fr_calib_copy",
                      "fr_calib_read"):
             getattr(L, name).restype = ctypes.c_int
@@ -220,6 +222,28 @@ def fr_draft_logits(H, W, z_out=None, stream=None):
     _check(lib().fr_draft_logits(_ptr(H), M, d, _ptr(W), V_rows, _ptr(z_out), _stream(stream)),
            "fr_draft_logits")
     return z_out
+
+
+def fr_draft_topk_multi(H_blocks, W_sub, idx_map, k: int, workspace, token_ids=None, logp=None, stream=None):
+    """fr_draft_topk over several equally shaped blocks of hidden states (a list of [rows, d]
+    tensors) against one W_sub, in one launch when they have at most 16 rows together."""
+    for h in H_blocks:
+        _bf16_matrix(h, "H block")
+    rows, d = H_blocks[0].shape
+    if any(h.shape != (rows, d) for h in H_blocks):
+        raise ValueError("all blocks of hidden states must have the same shape")
+    _bf16_matrix(W_sub, "W_sub")
+    M = rows * len(H_blocks)
+    if token_ids is None:
+        token_ids = torch.empty((M, k), dtype=torch.int32, device=W_sub.device)
+    if logp is None:
+        logp = torch.empty((M, k), dtype=torch.float32, device=W_sub.device)
+    ptrs = (ctypes.c_void_p * len(H_blocks))(*[h.data_ptr() for h in H_blocks])
+    _check(lib().fr_draft_topk_multi(ptrs, len(H_blocks), rows, d, _ptr(W_sub), _ptr(idx_map), W_sub.shape[0], k,
+                                     _ptr(token_ids), _ptr(logp), _ptr(workspace),
+                                     workspace.numel() * workspace.element_size(), _stream(stream)),
+           "fr_draft_topk_multi")
+    return token_ids, logp
 
 
 def fr_tiled_bytes(V_sub: int, d: int) -> int:

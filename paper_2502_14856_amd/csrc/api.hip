@@ -53,7 +53,8 @@ fr_status check_head_args(const void *H, int64_t M, int64_t d, const void *W, in
 
 fr_status head_topk(const void *H, int64_t M, int64_t d, const void *W, const int32_t *idx_map,
                     int64_t V_rows, int32_t k, int32_t *token_ids, float *logp, void *workspace,
-                    size_t workspace_bytes, fr_stream stream, const fr_tuning *tuning, bool tiled = false) {
+                    size_t workspace_bytes, fr_stream stream, const fr_tuning *tuning, bool tiled = false,
+                    const long long *row_delta = nullptr) {
     fr_status st = check_head_args(H, M, d, W, V_rows, k);
     if (st != FR_OK) return st;
     if (!token_ids || !logp || !workspace) return FR_ERR_INVALID_ARG;
@@ -68,6 +69,9 @@ fr_status head_topk(const void *H, int64_t M, int64_t d, const void *W, const in
     HeadProblem p{};
     p.W = W;
     p.tiled = tiled;
+    p.scattered_rows = row_delta != nullptr;
+    if (row_delta)
+        for (int m = 0; m < 16; ++m) p.row_delta[m] = row_delta[m];
     p.idx_map = idx_map;
     p.d = static_cast<int>(d);
     p.V_rows = static_cast<int>(V_rows);
@@ -88,6 +92,7 @@ fr_status head_topk(const void *H, int64_t M, int64_t d, const void *W, const in
         path = 3;
     }
     if (path == 0) path = (M <= kSkinnyMaxM && skinny_fits((int)M, (int)d, k)) ? 3 : 2;
+    if (row_delta && path == 2) return FR_ERR_UNSUPPORTED;
     const bool two_launch = tuning && tuning->two_launch;
     const bool stream_only = tuning && tuning->stream_only;
 
@@ -190,6 +195,36 @@ fr_status fr_workspace_init(void *workspace, size_t workspace_bytes, fr_stream s
     if (st != FR_OK) return st;
     return launch_fill_u32(reinterpret_cast<unsigned *>(static_cast<char *>(workspace) + kWorkspaceHeaderBytes),
                            mail / 4, 0xFFFFFFFFu, static_cast<hipStream_t>(stream));
+}
+
+fr_status fr_draft_topk_multi(const void *const *H_blocks, int32_t n_blocks, int64_t rows_per_block, int64_t d,
+                              const void *W_sub, const int32_t *idx_map, int64_t V_sub, int32_t k,
+                              int32_t *token_ids, float *logp, void *workspace, size_t workspace_bytes,
+                              fr_stream stream) {
+    if (!H_blocks || n_blocks < 1 || n_blocks > 16 || rows_per_block < 1) return FR_ERR_INVALID_ARG;
+    for (int32_t b = 0; b < n_blocks; ++b)
+        if (!H_blocks[b]) return FR_ERR_INVALID_ARG;
+        else if (!aligned16(H_blocks[b])) return FR_ERR_ALIGNMENT;
+    const int64_t M = static_cast<int64_t>(n_blocks) * rows_per_block;
+    fr_status st = check_head_args(H_blocks[0], M, d, W_sub, V_sub, k);
+    if (st != FR_OK) return st;
+    if (!token_ids || !logp || !workspace) return FR_ERR_INVALID_ARG;
+    if (M <= kSkinnyMaxM && skinny_fits((int)M, (int)d, k)) {
+        // one launch: the skinny kernel takes the rows where they are
+        long long delta[16] = {0};
+        for (int64_t m = 0; m < M; ++m)
+            delta[m] = (static_cast<const char *>(H_blocks[m / rows_per_block]) - static_cast<const char *>(H_blocks[0])) +
+                       (m % rows_per_block) * d * 2;
+        return head_topk(H_blocks[0], M, d, W_sub, idx_map, V_sub, k, token_ids, logp, workspace, workspace_bytes,
+                         stream, nullptr, false, delta);
+    }
+    // too many rows for the skinny kernel: one call per block
+    for (int32_t b = 0; b < n_blocks; ++b) {
+        st = head_topk(H_blocks[b], rows_per_block, d, W_sub, idx_map, V_sub, k, token_ids + b * rows_per_block * k,
+                       logp + b * rows_per_block * k, workspace, workspace_bytes, stream, nullptr);
+        if (st != FR_OK) return st;
+    }
+    return FR_OK;
 }
 
 fr_status fr_workspace_check(const void *workspace, size_t workspace_bytes, int32_t *timed_out,

@@ -28,7 +28,9 @@ struct WorkspaceView {
 };
 
 struct HeadProblem {
-    const void *H;        // bf16 [M, d]
+    const void *H;        // bf16 [M, d]; or, with scattered_rows, row m starts row_delta[m] bytes from H
+    bool scattered_rows;  // (skinny kernel only, M <= 16)
+    long long row_delta[16];
     const void *W;        // bf16 [V_rows, d] row-major, or the tiled layout of fr_build_subset_tiled
     bool tiled;
     const int *idx_map;   // nullable

@@ -50,6 +50,7 @@ constexpr int kRowsPerLane = 4;   // rows served by one lane
 constexpr int kLanesAlongD = 16;  // lanes of a row slot (one DPP row)
 
 struct SkinnyArgs {
+    long long row_delta[16];   // byte offset of row m of H from `H` (the rows may sit in several blocks)
     const u32x4 *H;
     const u32x4 *W;
     const int *idx_map;
@@ -213,12 +214,11 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     constexpr int kHRowsMax = SKEW ? 12 : 16;   // (the skewed build's LDS holds at most 11 rows of H)
     const GlobalBytes Hb = (GlobalBytes)a.H;
     const unsigned hcol = (unsigned)min(tid, a.d8 - 1) * 16u;   // clamped: always a valid address
-    const unsigned hrow_bytes = (unsigned)a.d8 * 16u;
     u32x4 hpre[kHRowsMax];
 #pragma unroll
     for (int m = 0; m < kHRowsMax; ++m)
-        if (m < hrows)   // wave-uniform; rows past M (zero padding) re-read the last row
-            hpre[m] = *reinterpret_cast<GlobalVec>(Hb + (unsigned)min(m, a.M - 1) * hrow_bytes + hcol);
+        if (m < hrows)   // wave-uniform; rows past M (zero padding) re-read row 0
+            hpre[m] = *reinterpret_cast<GlobalVec>(Hb + (m < a.M ? a.row_delta[m] : 0ll) + hcol);
     u32x4 wb[DEPTH][kRowsPerLane];
     unsigned wo[kRowsPerLane];
     const int first_pass = (int)blockIdx.x;
@@ -237,12 +237,15 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     for (int m = 0; m < kHRowsMax; ++m)
         if (m < hrows && tid < hcols)
             H_lds[m * hpitch + tid] = (tid < a.d8 && m < a.M) ? hpre[m] : zero_u32x4();
-    for (int c = tid + NT; c < hcols; c += NT)   // columns past the first NT: not held in registers
-        for (int m = 0; m < hrows; ++m) {
-            u32x4 v = zero_u32x4();
-            if (m < a.M && c < a.d8) v = a.H[(size_t)m * a.d8 + c];
-            H_lds[m * hpitch + c] = v;
-        }
+    for (int c = tid + NT; c < hcols; c += NT) {   // columns past the first NT: not held in registers
+#pragma unroll
+        for (int m = 0; m < 16; ++m)
+            if (m < hrows) {
+                u32x4 v = zero_u32x4();
+                if (m < a.M && c < a.d8) v = *reinterpret_cast<GlobalVec>(Hb + a.row_delta[m] + (unsigned)c * 16u);
+                H_lds[m * hpitch + c] = v;
+            }
+    }
     // (the running state needs no reset: a workgroup's first pass overwrites all of it)
     __syncthreads();
     stamp(1);
@@ -585,6 +588,8 @@ fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hip
 
     SkinnyArgs a{};
     a.H = static_cast<const u32x4 *>(p.H);
+    for (int m = 0; m < 16; ++m)
+        a.row_delta[m] = p.scattered_rows ? p.row_delta[m] : static_cast<long long>(m) * p.d * 2;
     a.W = static_cast<const u32x4 *>(p.W);
     a.idx_map = p.idx_map;
     a.M = p.M;

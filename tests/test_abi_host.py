@@ -140,3 +140,17 @@ def test_beam_glue_rejects_bad_arguments_before_any_launch():
     assert select(hs=0) == INVALID and select(m=0) == INVALID
     assert select(N=0) == INVALID and select(K=0) == INVALID and select(N=50, K=60) == INVALID
     assert select(N=5000) == UNSUPPORTED and select(N=4096, K=2000) == UNSUPPORTED
+
+
+def test_multi_block_entry_rejects_bad_arguments():
+    L = fr.lib()
+    two = (ctypes.c_void_p * 2)(0x1000, 0x9000)
+    bad = (ctypes.c_void_p * 2)(0x1000, 0)
+    odd = (ctypes.c_void_p * 2)(0x1000, 0x9008)
+
+    def call(ptrs=two, n=2, rows=5, d=4096, W=0x20000, V=32768, k=10, ids=0x3000, lp=0x4000, ws=0x5000):
+        return L.fr_draft_topk_multi(ptrs, n, rows, d, W, 0, V, k, ids, lp, ws, 1 << 26, None)
+
+    assert call(ptrs=None) == INVALID and call(n=0) == INVALID and call(n=17) == INVALID
+    assert call(rows=0) == INVALID and call(ptrs=bad) == INVALID and call(ptrs=odd) == ALIGN
+    assert call(k=0) == INVALID and call(W=0) == INVALID and call(ids=0) == INVALID

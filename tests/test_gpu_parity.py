@@ -327,3 +327,30 @@ def test_skewed_rows_between_neighbouring_workgroups(M, k, skew, exact):
     _sync()
     check_topk_against_oracle(ids_g.cpu().numpy(), lp_g.cpu().numpy(), z_o, idx_o, ids_o, lp_o)
     assert fr.fr_workspace_check(ws) is False
+
+
+@pytest.mark.parametrize("n_blocks,rows,k", [(4, 1, 10), (5, 3, 10), (2, 8, 16), (1, 10, 10), (3, 20, 10)])
+def test_hidden_states_in_several_blocks(n_blocks, rows, k):
+    # fr_draft_topk_multi: the rows of H sit in separately allocated blocks (several draft heads
+    # against one W_sub); the result must be what the stacked problem gives, bit for bit for the
+    # single-launch path (the kernel sees the same rows in the same order).
+    _say("several blocks of hidden states", n_blocks, rows, k)
+    V, V_sub, d = 6000, 3000, 512
+    W, _, r = _case(V, d, 1, 41)
+    W_o, idx_o = oracle.build_subset(W, r, V_sub)
+    W_g, idx_g = fr.fr_build_subset(to_dev_bf16(W), to_dev_i32(r), V_sub)
+    blocks = [make_hidden(rows, d, 50 + b) for b in range(n_blocks)]
+    pads = [torch.empty(1000 * (b + 1), device="cuda") for b in range(n_blocks)]   # keep the blocks apart
+    dev = [to_dev_bf16(h) for h in blocks]
+    H_all = np.concatenate(blocks, axis=0)
+    M = n_blocks * rows
+    ws = fr.new_workspace(M, d, V, k)
+    ids_m, lp_m = fr.fr_draft_topk_multi(dev, W_g, idx_g, k, ws)
+    ids_s, lp_s = fr.fr_draft_topk(to_dev_bf16(H_all), W_g, idx_g, k, ws)
+    _sync()
+    ids_o, lp_o, z_o = oracle.draft_topk(H_all, W_o, idx_o, k, want_logits=True)
+    check_topk_against_oracle(ids_m.cpu().numpy(), lp_m.cpu().numpy(), z_o, idx_o, ids_o, lp_o)
+    if M <= 16:
+        assert np.array_equal(ids_m.cpu().numpy(), ids_s.cpu().numpy())
+        assert np.array_equal(lp_m.cpu().numpy().view(np.uint32), lp_s.cpu().numpy().view(np.uint32))
+    del pads
