@@ -1,4 +1,4 @@
-"""ctypes front end of the CPU oracle (``frspec_oracle.c``, ``beam_oracle.c``).
+"""ctypes front end of the CPU oracle (``frspec_oracle.c``, ``beam_oracle.c``, ``freq_oracle.c``).
 
 TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by the smoke check and by the
 benchmark's cpu_baseline leg.  The GPU package never imports this module and
@@ -17,7 +17,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "frspec_oracle.c")
-_SRCS = [_SRC, os.path.join(_HERE, "beam_oracle.c")]
+_SRCS = [_SRC, os.path.join(_HERE, "beam_oracle.c"), os.path.join(_HERE, "freq_oracle.c")]
 _LIB = os.path.join(_HERE, "liboracle.so")
 
 _lib = None
@@ -49,6 +49,10 @@ def _load():
         lib.oracle_num_threads.argtypes = []
         lib.oracle_beam_expand.argtypes = [vp, vp, i64, i32, vp, vp, i32, vp, vp, vp, i64, vp, vp, vp]
         lib.oracle_tree_select.argtypes = [vp, vp, vp, i64, i32, vp, vp, vp, vp, vp]
+        lib.oracle_count_tokens.argtypes = [vp, i64, i64, vp, vp]
+        lib.oracle_rank_tokens.argtypes = [vp, i64, vp]
+        for name in ("oracle_count_tokens", "oracle_rank_tokens"):
+            getattr(lib, name).restype = ctypes.c_int
         for name in ("oracle_build_subset", "oracle_logits_f32", "oracle_logits_f64",
                      "oracle_log_softmax", "oracle_topk", "oracle_draft_topk",
                      "oracle_full_topk", "oracle_num_threads", "oracle_beam_expand",
@@ -210,3 +214,26 @@ def tree_select(hist_score, hist_token, hist_parent, K):
                                       _p(sel_token), _p(sel_parent), _p(sel_depth), _p(mask)),
            "oracle_tree_select")
     return sel_index, sel_token, sel_parent, sel_depth, mask
+
+
+def count_tokens(tokens, V, counts=None):
+    """Corpus-level token statistics (Section 3.2): adds the occurrences of every id of the
+    stream to counts (int64 [V], created zeroed if not given).  Returns (counts, n_bad) where
+    n_bad is the number of ids outside [0, V) that were skipped."""
+    tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+    if counts is None:
+        counts = np.zeros(V, dtype=np.int64)
+    assert counts.dtype == np.int64 and counts.shape == (V,) and counts.flags.c_contiguous
+    bad = ctypes.c_int64(0)
+    _check(_load().oracle_count_tokens(_p(tokens), tokens.size, V, _p(counts), ctypes.addressof(bad)),
+           "oracle_count_tokens")
+    return counts, int(bad.value)
+
+
+def rank_tokens(counts):
+    """All ids ordered by count descending, equal counts by lower id: the frequency ranking
+    from which V_high is taken (Section 3.2)."""
+    counts = np.ascontiguousarray(counts, dtype=np.int64)
+    out = np.empty(counts.shape[0], dtype=np.int32)
+    _check(_load().oracle_rank_tokens(_p(counts), counts.shape[0], _p(out)), "oracle_rank_tokens")
+    return out
