@@ -167,6 +167,22 @@ def main() -> int:
     t_phase = timed(draft_phase, 100, 5)
     t_select = timed(lambda i: fr.fr_tree_select(*hist, cap, K), 300, 20)
 
+    # ---- the step before the path: corpus statistics -> ranking (Section 3.2), on a synthetic
+    # Zipf(1.1) stream of 2^26 token ids (the paper counts 1e9 tokens of SlimPajama offline)
+    n_tok = 1 << 26
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(20250214)
+    pz = 1.0 / torch.arange(1, V + 1, device="cuda", dtype=torch.float64) ** cfg.zipf_s
+    cdf = torch.cumsum(pz / pz.sum(), 0)
+    draws = torch.searchsorted(cdf, torch.rand(n_tok, device="cuda", dtype=torch.float64, generator=gen))
+    tokens = torch.randperm(V, device="cuda", generator=gen)[draws.clamp_(max=V - 1)].to(torch.int32)
+    del draws
+    counts = torch.zeros(V, dtype=torch.int64, device="cuda")
+    t_count = timed(lambda i: fr.fr_count_tokens(tokens, V, counts=counts), 10, 2)
+    ranked_out = torch.empty(V, dtype=torch.int32, device="cuda")
+    t_rank = timed(lambda i: fr.fr_rank_tokens(counts, freq_ranked_ids=ranked_out), 10, 2)
+    del tokens
+
     bytes_per_call = V_sub * d * 2
     achieved = bytes_per_call / t_step / 1e9
     traffic = _profile_traffic()
@@ -225,6 +241,9 @@ def main() -> int:
             "draft_phase_depth6_us": t_phase * 1e6,
             "draft_phase_note": "6 x (fr_draft_topk + fr_beam_expand) + fr_tree_select (K=60), width 10; "
                                 "the draft model's transformer layer is not part of this build",
+            "count_tokens_gtok_per_s": n_tok / t_count / 1e9,
+            "count_tokens_us_per_2p26": t_count * 1e6,
+            "rank_tokens_us": t_rank * 1e6,
             "plain_read_kernel_us": t_read * 1e6,
             "plain_read_kernel_gbps": bytes_per_call / t_read / 1e9,
             "host_wall_s_timed_region": wall,

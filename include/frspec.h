@@ -260,6 +260,22 @@ fr_status fr_draft_topk_tiled(const void *H, int64_t M, int64_t d, const void *W
 
 
 /*
+ * Corpus-level token statistics (Section 3.2): the step that produces the ranking which
+ * fr_build_subset consumes.
+ *   fr_count_tokens  counts[t] += occurrences of t in tokens[0..n_tokens); ids outside [0, V)
+ *                    are skipped and *dev_error_flag (optional) is set.  `counts` (int64 [V])
+ *                    accumulates over calls: zero it before the first one.  `tokens` must be
+ *                    16-byte aligned.
+ *   fr_rank_tokens   freq_ranked_ids[0..V) = all ids by count descending, equal counts by
+ *                    lower id (counts must be >= 0).  V <= 2^22, else FR_ERR_UNSUPPORTED.
+ * All device pointers; asynchronous on `stream`.
+ */
+fr_status fr_count_tokens(const int32_t *tokens, int64_t n_tokens, int64_t V, int64_t *counts,
+                          int32_t *dev_error_flag, fr_stream stream);
+fr_status fr_rank_tokens(const int64_t *counts, int64_t V, int32_t *freq_ranked_ids,
+                         fr_stream stream);
+
+/*
  * Bandwidth calibration kernels: a plain copy and a plain read of `bytes` bytes
  * (multiple of 16), used to scale hardware counters and to report what a trivial
  * streaming kernel achieves on the same machine.  `sink` receives one 16-byte value

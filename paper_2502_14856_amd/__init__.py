@@ -14,11 +14,13 @@ from .binding import (  # noqa: F401
     fr_build_subset_tiled,
     fr_calib_copy,
     fr_calib_read,
+    fr_count_tokens,
     fr_draft_logits,
     fr_draft_topk,
     fr_draft_topk_multi,
     fr_draft_topk_tiled,
     fr_full_topk,
+    fr_rank_tokens,
     fr_strerror,
     fr_tiled_bytes,
     fr_tree_select,

@@ -66,6 +66,8 @@ def lib():
         L.fr_draft_logits.argtypes = [vp, i64, i64, vp, i64, vp, vp]
         L.fr_draft_topk_multi.argtypes = [ctypes.POINTER(ctypes.c_void_p), i32, i64, i64, vp, vp, i64, i32, vp, vp,
                                           vp, sz, vp]
+        L.fr_count_tokens.argtypes = [vp, i64, i64, vp, vp, vp]
+        L.fr_rank_tokens.argtypes = [vp, i64, vp, vp]
         L.fr_tiled_bytes.argtypes = [i64, i64]
         L.fr_tiled_bytes.restype = sz
         L.fr_build_subset_tiled.argtypes = [vp, i64, i64, vp, i64, vp, vp, vp, vp]
@@ -76,7 +78,7 @@ def lib():
         L.fr_calib_copy.argtypes = [vp, vp, sz, vp]
         L.fr_calib_read.argtypes = [vp, sz, vp, vp]
         for name in ("fr_build_subset", "fr_workspace_init", "fr_workspace_check", "fr_draft_topk", "fr_draft_topk_tuned",
-                     "fr_full_topk", "fr_draft_logits", "fr_beam_expand", "fr_tree_select", "fr_draft_topk_multi", "fr_build_subset_tiled",
+                     "fr_full_topk", "fr_draft_logits", "fr_beam_expand", "fr_tree_select", "fr_draft_topk_multi", "fr_count_tokens", "fr_rank_tokens", "fr_build_subset_tiled",
                      "fr_draft_topk_tiled", "fr_calib_copy",
                      "fr_calib_read"):
             getattr(L, name).restype = ctypes.c_int
@@ -244,6 +246,31 @@ def fr_draft_topk_multi(H_blocks, W_sub, idx_map, k: int, workspace, token_ids=N
                                      workspace.numel() * workspace.element_size(), _stream(stream)),
            "fr_draft_topk_multi")
     return token_ids, logp
+
+
+def fr_count_tokens(tokens, V: int, counts=None, dev_error_flag=None, stream=None):
+    """Adds the occurrences of every id of the int32 stream to counts (int64 [V], created zeroed
+    if not given).  Section 3.2: corpus-level token statistics."""
+    _dev(tokens, torch.int32, "tokens")
+    if counts is None:
+        counts = torch.zeros(V, dtype=torch.int64, device=tokens.device)
+    _dev(counts, torch.int64, "counts")
+    if counts.numel() < V:
+        raise ValueError("counts must hold V entries")
+    _check(lib().fr_count_tokens(_ptr(tokens), tokens.numel(), V, _ptr(counts), _ptr(dev_error_flag),
+                                 _stream(stream)), "fr_count_tokens")
+    return counts
+
+
+def fr_rank_tokens(counts, freq_ranked_ids=None, stream=None):
+    """All ids by count descending, equal counts by lower id (int32 [V])."""
+    _dev(counts, torch.int64, "counts")
+    V = counts.numel()
+    if freq_ranked_ids is None:
+        freq_ranked_ids = torch.empty(V, dtype=torch.int32, device=counts.device)
+    _check(lib().fr_rank_tokens(_ptr(counts), V, _ptr(_dev(freq_ranked_ids, torch.int32, "freq_ranked_ids")),
+                                _stream(stream)), "fr_rank_tokens")
+    return freq_ranked_ids
 
 
 def fr_tiled_bytes(V_sub: int, d: int) -> int:

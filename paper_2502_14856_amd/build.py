@@ -18,7 +18,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libfrspec.so")
 
-SOURCES = ["api.hip", "skinny.hip", "mfma.hip", "merge.hip", "gather.hip", "glue.hip", "calib.hip"]
+SOURCES = ["api.hip", "skinny.hip", "mfma.hip", "merge.hip", "gather.hip", "glue.hip", "freq.hip", "calib.hip"]
 
 # Packed fp32 VALU instructions are switched off for every device translation unit.
 HIP_FLAGS = [
@@ -46,7 +46,7 @@ def _compile(src: str, extra) -> str:
 def build(verbose: bool = False, save_temps: bool = False) -> str:
     os.makedirs(BUILD, exist_ok=True)
     extra = ["-save-temps=obj"] if save_temps else []
-    with ThreadPoolExecutor(max_workers=min(7, os.cpu_count() or 1)) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
         objs = list(ex.map(lambda s: _compile(s, extra), SOURCES))
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)

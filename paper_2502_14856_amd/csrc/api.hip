@@ -325,6 +325,23 @@ fr_status fr_tree_select(const float *hist_score, const int32_t *hist_token,
                               sel_parent, sel_depth, tree_mask, static_cast<hipStream_t>(stream));
 }
 
+fr_status fr_count_tokens(const int32_t *tokens, int64_t n_tokens, int64_t V, int64_t *counts,
+                          int32_t *dev_error_flag, fr_stream stream) {
+    if (!counts || (!tokens && n_tokens > 0) || n_tokens < 0 || V < 1 || V > INT32_MAX) return FR_ERR_INVALID_ARG;
+    if (tokens && !aligned16(tokens)) return FR_ERR_ALIGNMENT;
+    if ((reinterpret_cast<uintptr_t>(counts) & 7u) != 0) return FR_ERR_ALIGNMENT;
+    if (n_tokens == 0) return FR_OK;
+    return launch_count_tokens(tokens, n_tokens, static_cast<int>(V), reinterpret_cast<unsigned long long *>(counts),
+                               dev_error_flag, static_cast<hipStream_t>(stream));
+}
+
+fr_status fr_rank_tokens(const int64_t *counts, int64_t V, int32_t *freq_ranked_ids, fr_stream stream) {
+    if (!counts || !freq_ranked_ids || V < 1 || V > INT32_MAX) return FR_ERR_INVALID_ARG;
+    if (V > (1 << 22)) return FR_ERR_UNSUPPORTED;   // the all-pairs ranking is meant for vocabularies
+    return launch_rank_tokens(reinterpret_cast<const long long *>(counts), static_cast<int>(V), freq_ranked_ids,
+                              static_cast<hipStream_t>(stream));
+}
+
 fr_status fr_calib_copy(void *dst, const void *src, size_t bytes, fr_stream stream) {
     if (!dst || !src || (bytes % 16) != 0) return FR_ERR_INVALID_ARG;
     if (!aligned16(dst) || !aligned16(src)) return FR_ERR_ALIGNMENT;

@@ -87,6 +87,11 @@ fr_status launch_tree_select(const float *hist_score, const int *hist_token, con
                              int *sel_index, int *sel_token, int *sel_parent, int *sel_depth,
                              unsigned char *tree_mask, hipStream_t s);
 
+// freq.hip: token counting and frequency ranking.
+fr_status launch_count_tokens(const int *tokens, long long n, int V, unsigned long long *counts, int *flag,
+                              hipStream_t s);
+fr_status launch_rank_tokens(const long long *counts, int V, int *ranked, hipStream_t s);
+
 // calib.hip
 fr_status launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
 fr_status launch_read(const void *src, size_t bytes, void *sink, hipStream_t s);

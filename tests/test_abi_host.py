@@ -154,3 +154,18 @@ def test_multi_block_entry_rejects_bad_arguments():
     assert call(ptrs=None) == INVALID and call(n=0) == INVALID and call(n=17) == INVALID
     assert call(rows=0) == INVALID and call(ptrs=bad) == INVALID and call(ptrs=odd) == ALIGN
     assert call(k=0) == INVALID and call(W=0) == INVALID and call(ids=0) == INVALID
+
+
+def test_token_statistics_reject_bad_arguments():
+    L = fr.lib()
+    UNSUPPORTED = -5
+    assert L.fr_count_tokens(0x1000, 10, 100, 0, None, None) == INVALID
+    assert L.fr_count_tokens(0, 10, 100, 0x2000, None, None) == INVALID
+    assert L.fr_count_tokens(0x1000, -1, 100, 0x2000, None, None) == INVALID
+    assert L.fr_count_tokens(0x1000, 10, 0, 0x2000, None, None) == INVALID
+    assert L.fr_count_tokens(0x1004, 10, 100, 0x2000, None, None) == ALIGN
+    assert L.fr_count_tokens(0x1000, 10, 100, 0x2004, None, None) == ALIGN
+    assert L.fr_count_tokens(0x1000, 0, 100, 0x2000, None, None) == 0          # nothing to do, nothing launched
+    assert L.fr_rank_tokens(0, 100, 0x2000, None) == INVALID
+    assert L.fr_rank_tokens(0x1000, 0, 0x2000, None) == INVALID
+    assert L.fr_rank_tokens(0x1000, (1 << 22) + 1, 0x2000, None) == UNSUPPORTED
