@@ -895,9 +895,10 @@ __device__ __forceinline__ void merge_rows_mailbox(const Mailbox &mb, const Part
         }
         __syncthreads();
 
-        // ---- every wavefront has its records: empty them for the next call (each record
-        // by the wavefront that owns its list position; the statistics by the last one)
-        if (wave < NW) {
+        // Every wavefront has its records: they are emptied for the next call, each record by
+        // the wavefront that owns its list position, the statistics by the last one.  The first
+        // wavefront does that after the row's outputs are on their way.
+        auto empty_my_records = [&]() {
 #pragma unroll
             for (int q = 0; q < HPL; ++q) {
                 const int g = lane + kWave * q;
@@ -910,7 +911,8 @@ __device__ __forceinline__ void merge_rows_mailbox(const Mailbox &mb, const Part
                     if (wave == NW - 1) publish(mb.st + mail_st_index(m, g), kMailEmpty);
                 }
             }
-        }
+        };
+        if (wave > 0 && wave < NW) empty_my_records();
 
         const int n = __builtin_amdgcn_readfirstlane((int)ms->count);
         if (n <= kWave) {
@@ -933,10 +935,12 @@ __device__ __forceinline__ void merge_rows_mailbox(const Mailbox &mb, const Part
                     token_ids[(size_t)m * k + lane] = INT_MAX;
                     logp[(size_t)m * k + lane] = kNegInf;
                 }
+                empty_my_records();
             }
         } else {
             // Too many survivors (heavily tied values): hand the row to the general merge
             // through the plain partial arrays.
+            if (wave == 0) empty_my_records();
             if (wave < NW) {
 #pragma unroll
                 for (int q = 0; q < HPL; ++q) {
