@@ -165,6 +165,22 @@ def main() -> int:
             off += Mstep * k
         return fr.fr_tree_select(*hist, off, K)
     t_phase = timed(draft_phase, 100, 5)
+
+    def draft_phase_fused(i):
+        ns, nh, off = node_score[:1], node_hist[:1], 0
+        for step in range(depth):
+            Mstep = 1 if step == 0 else width
+            _, _, ns, _, nh = fr.fr_draft_step(H[:Mstep], copies[(i * depth + step) % N_COPIES], idx_map, k, ns, nh,
+                                               min(width, Mstep * k), *hist, off, ws, token_ids=ids[:Mstep],
+                                               logp=logp[:Mstep], next_score=nxt[0], next_token=nxt[1],
+                                               next_hist=nxt[2])
+            off += Mstep * k
+        return fr.fr_tree_select(*hist, off, K)
+    t_phase_fused = timed(draft_phase_fused, 100, 5)
+    t_step_fused = timed(lambda i: fr.fr_draft_step(H, copies[i % N_COPIES], idx_map, k, node_score, node_hist, width,
+                                                    *hist, k, ws, token_ids=ids, logp=logp, next_score=nxt[0],
+                                                    next_token=nxt[1], next_hist=nxt[2]),
+                         max(50, args.steps // 4), 20)
     t_select = timed(lambda i: fr.fr_tree_select(*hist, cap, K), 300, 20)
 
     # ---- the step before the path: corpus statistics -> ranking (Section 3.2), on a synthetic
@@ -239,7 +255,10 @@ def main() -> int:
             "beam_expand_us": t_expand * 1e6,
             "tree_select_us": t_select * 1e6,
             "draft_phase_depth6_us": t_phase * 1e6,
-            "draft_phase_note": "6 x (fr_draft_topk + fr_beam_expand) + fr_tree_select (K=60), width 10; "
+            "draft_step_fused_us": t_step_fused * 1e6,
+            "draft_phase_fused_depth6_us": t_phase_fused * 1e6,
+            "draft_phase_note": "6 x (fr_draft_topk + fr_beam_expand) + fr_tree_select (K=60), width 10; fused = "
+                                "6 x fr_draft_step (expansion inside the LM head's launch) + fr_tree_select; "
                                 "the draft model's transformer layer is not part of this build",
             "count_tokens_gtok_per_s": n_tok / t_count / 1e9,
             "count_tokens_us_per_2p26": t_count * 1e6,

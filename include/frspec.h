@@ -78,7 +78,7 @@ size_t fr_workspace_bytes(int64_t M, int64_t d, int64_t V_rows, int32_t k);
 
 /*
  * Prepares a freshly allocated workspace: clears the arrival counters of the single-launch
- * kernels and marks every record of the result mailbox empty (about 1.1 MiB is written).
+ * kernels and marks every record of the result mailboxes empty (about 1.1 MiB is written).
  * Call once per workspace before its first use,
  * and again if a call using it was ever abandoned mid-flight.  Every completed call
  * leaves the workspace ready for the next one.  Calls that share a workspace must be
@@ -167,6 +167,23 @@ fr_status fr_beam_expand(const float *logp, const int32_t *token_ids, int64_t M,
                          float *hist_score, int32_t *hist_token, int32_t *hist_parent,
                          int64_t hist_offset, float *next_score, int32_t *next_token,
                          int32_t *next_hist, fr_stream stream);
+
+/*
+ * fr_draft_topk and fr_beam_expand as one call: the draft LM head on the M nodes of a draft
+ * step, then the expansion of the beam search with the head's own outputs.  Arguments as in
+ * those two calls; token_ids / logp [M, k] are still written.  For M <= 16, k <= 16 (and a
+ * device of at most 256 compute units) the expansion runs inside the LM head's launch: the
+ * workgroup that merges the first row collects every row's result and appends, ranks and
+ * returns the next nodes, which saves a launch per draft step (the "short-duration tasks" of
+ * Section 3.1).  Otherwise the two launches follow each other on `stream`.
+ */
+fr_status fr_draft_step(const void *H, int64_t M, int64_t d, const void *W_sub,
+                        const int32_t *idx_map, int64_t V_sub, int32_t k, const float *node_score,
+                        const int32_t *node_hist, int32_t width, float *hist_score,
+                        int32_t *hist_token, int32_t *hist_parent, int64_t hist_offset,
+                        int32_t *token_ids, float *logp, float *next_score, int32_t *next_token,
+                        int32_t *next_hist, void *workspace, size_t workspace_bytes,
+                        fr_stream stream);
 
 /*
  * The draft tree (Section 2: "select the top K probability tokens from the beam search

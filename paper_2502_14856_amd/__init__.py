@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     fr_calib_read,
     fr_count_tokens,
     fr_draft_logits,
+    fr_draft_step,
     fr_draft_topk,
     fr_draft_topk_multi,
     fr_draft_topk_tiled,

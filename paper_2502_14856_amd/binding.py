@@ -73,12 +73,14 @@ def lib():
         L.fr_build_subset_tiled.argtypes = [vp, i64, i64, vp, i64, vp, vp, vp, vp]
         L.fr_draft_topk_tiled.argtypes = [vp, i64, i64, vp, vp, i64, i32, vp, vp, vp, sz, vp,
                                           ctypes.POINTER(Tuning)]
+        L.fr_draft_step.argtypes = [vp, i64, i64, vp, vp, i64, i32, vp, vp, i32, vp, vp, vp, i64, vp, vp, vp, vp, vp,
+                                    vp, sz, vp]
         L.fr_beam_expand.argtypes = [vp, vp, i64, i32, vp, vp, i32, vp, vp, vp, i64, vp, vp, vp, vp]
         L.fr_tree_select.argtypes = [vp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp]
         L.fr_calib_copy.argtypes = [vp, vp, sz, vp]
         L.fr_calib_read.argtypes = [vp, sz, vp, vp]
         for name in ("fr_build_subset", "fr_workspace_init", "fr_workspace_check", "fr_draft_topk", "fr_draft_topk_tuned",
-                     "fr_full_topk", "fr_draft_logits", "fr_beam_expand", "fr_tree_select", "fr_draft_topk_multi", "fr_count_tokens", "fr_rank_tokens", "fr_build_subset_tiled",
+                     "fr_full_topk", "fr_draft_logits", "fr_beam_expand", "fr_tree_select", "fr_draft_step", "fr_draft_topk_multi", "fr_count_tokens", "fr_rank_tokens", "fr_build_subset_tiled",
                      "fr_draft_topk_tiled", "fr_calib_copy",
                      "fr_calib_read"):
             getattr(L, name).restype = ctypes.c_int
@@ -353,6 +355,44 @@ def fr_beam_expand(logp, token_ids, node_score, node_hist, width: int, hist_scor
                                 _ptr(_dev(next_hist, torch.int32, "next_hist")), _stream(stream)),
            "fr_beam_expand")
     return next_score, next_token, next_hist
+
+
+def fr_draft_step(H, W_sub, idx_map, k: int, node_score, node_hist, width: int, hist_score, hist_token,
+                  hist_parent, hist_offset: int, workspace, token_ids=None, logp=None, next_score=None,
+                  next_token=None, next_hist=None, stream=None):
+    """The draft LM head on the nodes of a draft step and the beam-search expansion, one call
+    (one launch for M <= 16, k <= 16).  Returns (token_ids, logp, next_score, next_token, next_hist)."""
+    _bf16_matrix(H, "H")
+    _bf16_matrix(W_sub, "W_sub")
+    M, d = H.shape
+    dev = H.device
+    if token_ids is None:
+        token_ids = torch.empty((M, k), dtype=torch.int32, device=dev)
+    if logp is None:
+        logp = torch.empty((M, k), dtype=torch.float32, device=dev)
+    if next_score is None:
+        next_score = torch.empty(width, dtype=torch.float32, device=dev)
+    if next_token is None:
+        next_token = torch.empty(width, dtype=torch.int32, device=dev)
+    if next_hist is None:
+        next_hist = torch.empty(width, dtype=torch.int32, device=dev)
+    for t, dt, name in ((node_score, torch.float32, "node_score"), (node_hist, torch.int32, "node_hist"),
+                        (hist_score, torch.float32, "hist_score"), (hist_token, torch.int32, "hist_token"),
+                        (hist_parent, torch.int32, "hist_parent"), (next_score, torch.float32, "next_score"),
+                        (next_token, torch.int32, "next_token"), (next_hist, torch.int32, "next_hist")):
+        _dev(t, dt, name)
+    if node_score.numel() < M or node_hist.numel() < M:
+        raise ValueError("node_score and node_hist must hold M entries")
+    if min(hist_score.numel(), hist_token.numel(), hist_parent.numel()) < hist_offset + M * k:
+        raise ValueError("history arrays are too short for hist_offset + M*k entries")
+    if min(next_score.numel(), next_token.numel(), next_hist.numel()) < width:
+        raise ValueError("next_* must hold `width` entries")
+    _check(lib().fr_draft_step(_ptr(H), M, d, _ptr(W_sub), _ptr(idx_map), W_sub.shape[0], k, _ptr(node_score),
+                               _ptr(node_hist), width, _ptr(hist_score), _ptr(hist_token), _ptr(hist_parent),
+                               hist_offset, _ptr(token_ids), _ptr(logp), _ptr(next_score), _ptr(next_token),
+                               _ptr(next_hist), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                               _stream(stream)), "fr_draft_step")
+    return token_ids, logp, next_score, next_token, next_hist
 
 
 def fr_tree_select(hist_score, hist_token, hist_parent, N: int, K: int, stream=None):

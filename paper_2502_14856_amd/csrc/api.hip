@@ -26,13 +26,14 @@ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline size_t round256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
 
 struct WorkspaceLayout {
-    size_t mail_rec_off, mail_st_off, ms_off, val_off, id_off, total;
+    size_t mail_rec_off, mail_st_off, step_rec_off, ms_off, val_off, id_off, total;
     WorkspaceLayout(int64_t M, int32_t k) {
         const size_t rows = static_cast<size_t>(M < kMatrixPathMaxM ? M : kMatrixPathMaxM);
         const size_t slots = static_cast<size_t>(kWorkspaceGridMax) * rows;
         size_t o = kWorkspaceHeaderBytes;
         mail_rec_off = o; o += kMailRecBytes;
         mail_st_off = o;  o += kMailStBytes;
+        step_rec_off = o; o += kStepRecBytes;
         ms_off = o;  o += round256(slots * 2 * sizeof(float));
         val_off = o; o += round256(slots * static_cast<size_t>(k) * sizeof(float));
         id_off = o;  o += round256(slots * static_cast<size_t>(k) * sizeof(int));
@@ -54,7 +55,7 @@ fr_status check_head_args(const void *H, int64_t M, int64_t d, const void *W, in
 fr_status head_topk(const void *H, int64_t M, int64_t d, const void *W, const int32_t *idx_map,
                     int64_t V_rows, int32_t k, int32_t *token_ids, float *logp, void *workspace,
                     size_t workspace_bytes, fr_stream stream, const fr_tuning *tuning, bool tiled = false,
-                    const long long *row_delta = nullptr) {
+                    const long long *row_delta = nullptr, const StepArgs *step = nullptr) {
     fr_status st = check_head_args(H, M, d, W, V_rows, k);
     if (st != FR_OK) return st;
     if (!token_ids || !logp || !workspace) return FR_ERR_INVALID_ARG;
@@ -79,6 +80,8 @@ fr_status head_topk(const void *H, int64_t M, int64_t d, const void *W, const in
     p.ws.ticket = reinterpret_cast<unsigned *>(ws);
     p.ws.mail_rec = reinterpret_cast<unsigned long long *>(ws + wl.mail_rec_off);
     p.ws.mail_st = reinterpret_cast<unsigned long long *>(ws + wl.mail_st_off);
+    p.ws.step_rec = reinterpret_cast<unsigned long long *>(ws + wl.step_rec_off);
+    p.step = step;
     p.ws.part_ms = reinterpret_cast<float *>(ws + wl.ms_off);
     p.ws.part_val = reinterpret_cast<float *>(ws + wl.val_off);
     p.ws.part_id = reinterpret_cast<int *>(ws + wl.id_off);
@@ -92,7 +95,7 @@ fr_status head_topk(const void *H, int64_t M, int64_t d, const void *W, const in
         path = 3;
     }
     if (path == 0) path = (M <= kSkinnyMaxM && skinny_fits((int)M, (int)d, k)) ? 3 : 2;
-    if (row_delta && path == 2) return FR_ERR_UNSUPPORTED;
+    if ((row_delta || step) && path == 2) return FR_ERR_UNSUPPORTED;
     const bool two_launch = tuning && tuning->two_launch;
     const bool stream_only = tuning && tuning->stream_only;
 
@@ -187,7 +190,7 @@ size_t fr_workspace_bytes(int64_t M, int64_t d, int64_t V_rows, int32_t k) {
 fr_status fr_workspace_init(void *workspace, size_t workspace_bytes, fr_stream stream) {
     if (!workspace) return FR_ERR_INVALID_ARG;
     if (!aligned16(workspace)) return FR_ERR_ALIGNMENT;
-    const size_t mail = kMailRecBytes + kMailStBytes;
+    const size_t mail = kMailRecBytes + kMailStBytes + kStepRecBytes;
     if (workspace_bytes < kWorkspaceHeaderBytes + mail) return FR_ERR_WORKSPACE;
     // arrival words: zero; mailbox: all ones (= every record empty)
     fr_status st = launch_fill_u32(static_cast<unsigned *>(workspace), kWorkspaceHeaderBytes / 4, 0u,
@@ -294,6 +297,40 @@ fr_status fr_draft_logits(const void *H, int64_t M, int64_t d, const void *W, in
         if (st != FR_OK) return st;
     }
     return FR_OK;
+}
+
+fr_status fr_draft_step(const void *H, int64_t M, int64_t d, const void *W_sub, const int32_t *idx_map,
+                        int64_t V_sub, int32_t k, const float *node_score, const int32_t *node_hist,
+                        int32_t width, float *hist_score, int32_t *hist_token, int32_t *hist_parent,
+                        int64_t hist_offset, int32_t *token_ids, float *logp, float *next_score,
+                        int32_t *next_token, int32_t *next_hist, void *workspace, size_t workspace_bytes,
+                        fr_stream stream) {
+    if (!node_score || !node_hist || !hist_score || !hist_token || !hist_parent || !next_score || !next_token ||
+        !next_hist)
+        return FR_ERR_INVALID_ARG;
+    if (width < 1 || hist_offset < 0 || hist_offset > INT32_MAX) return FR_ERR_INVALID_ARG;
+    if (M >= 1 && k >= 1 && (width > M * k || hist_offset + M * k > INT32_MAX)) return FR_ERR_INVALID_ARG;
+    StepArgs st{};
+    st.node_score = node_score;
+    st.node_hist = node_hist;
+    st.width = width;
+    st.hist_offset = hist_offset;
+    st.hist_score = hist_score;
+    st.hist_token = hist_token;
+    st.hist_parent = hist_parent;
+    st.next_score = next_score;
+    st.next_token = next_token;
+    st.next_hist = next_hist;
+    // one launch when the skinny kernel's mailbox merge applies; else the two calls one after the other
+    fr_status s = FR_ERR_UNSUPPORTED;
+    if (M <= kSkinnyMaxM && M * k <= 256)
+        s = head_topk(H, M, d, W_sub, idx_map, V_sub, k, token_ids, logp, workspace, workspace_bytes, stream, nullptr,
+                      false, nullptr, &st);
+    if (s != FR_ERR_UNSUPPORTED) return s;
+    s = head_topk(H, M, d, W_sub, idx_map, V_sub, k, token_ids, logp, workspace, workspace_bytes, stream, nullptr);
+    if (s != FR_OK) return s;
+    return fr_beam_expand(logp, token_ids, M, k, node_score, node_hist, width, hist_score, hist_token, hist_parent,
+                          hist_offset, next_score, next_token, next_hist, stream);
 }
 
 fr_status fr_beam_expand(const float *logp, const int32_t *token_ids, int64_t M, int32_t k,

@@ -8,6 +8,7 @@
 // candidates, and writes token ids and log-probabilities.
 #pragma once
 
+#include "internal.hpp"
 #include "wave_ops.hpp"
 
 namespace frspec {
@@ -772,6 +773,80 @@ __device__ __noinline__ void final_merge_general(Partials P, int G, int first, i
 }
 
 /*
+ * The beam-search expansion of a draft step (Section 2 of the paper) fused into the LM head's
+ * launch.  The merger of every row of H hands the row's k results on as records
+ * step_rec[m][t] = (logp bits << 32) | token, all ones while empty; the first merger, when
+ * its own rows are out, collects all M * k of them, forms the cumulative scores
+ * node_score[m] + logp, appends the candidates to the search history and returns the `width`
+ * best as the next nodes: what fr_beam_expand does in a launch of its own.
+ */
+
+// One wavefront; keys: LDS, at least M * k + 2 entries, 16-byte aligned.
+__device__ __forceinline__ void expand_step_fused(const StepArgs &st, int M, int k, unsigned long long *keys,
+                                                  unsigned *error) {
+    constexpr int CPL = kMailRows * kMailK / kWave;   // 4 candidates per lane at most
+    const int lane = lane_id(), C = M * k;
+    unsigned long long r[CPL];
+    int row[CPL], at[CPL];
+    bool inb[CPL];
+#pragma unroll
+    for (int q = 0; q < CPL; ++q) {
+        const int c = lane + kWave * q;
+        inb[q] = c < C;
+        row[q] = inb[q] ? c / k : 0;
+        at[q] = row[q] * kMailK + (inb[q] ? c - row[q] * k : 0);
+        r[q] = observe(st.rec + at[q]);
+    }
+    for (unsigned polls = 0;; ++polls) {
+        bool again = false;
+#pragma unroll
+        for (int q = 0; q < CPL; ++q)
+            if (inb[q] && r[q] == kMailEmpty) {
+                r[q] = observe(st.rec + at[q]);
+                again = true;
+            }
+        if (!__any(again)) break;
+        if (polls > kMailSpinLimit) {
+            if (lane == 0) __hip_atomic_store(error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            break;
+        }
+        __builtin_amdgcn_s_sleep(1);
+    }
+    float score[CPL];
+#pragma unroll
+    for (int q = 0; q < CPL; ++q) {
+        const int c = lane + kWave * q;
+        if (inb[q]) {
+            publish(st.rec + at[q], kMailEmpty);
+            score[q] = st.node_score[row[q]] + mail_hi(r[q]);   // the one rounding of the cumulative score
+            st.hist_score[st.hist_offset + c] = score[q];
+            st.hist_token[st.hist_offset + c] = (int)(unsigned)r[q];
+            st.hist_parent[st.hist_offset + c] = st.node_hist[row[q]];
+            keys[c] = make_key(key_hi_of(score[q]), ~(unsigned)c);
+        }
+    }
+    if (lane == 0) keys[C] = 0ull;
+    // (one wavefront: its LDS operations execute in order, no barrier needed)
+    const u64x2 *kp = reinterpret_cast<const u64x2 *>(keys);
+#pragma unroll
+    for (int q = 0; q < CPL; ++q) {
+        if (__ballot(inb[q]) == 0ull) continue;
+        const unsigned long long mine = inb[q] ? keys[lane + kWave * q] : ~0ull;
+        int rank = 0;
+        for (int j = 0; j < C; j += 2) {
+            const u64x2 two = kp[j >> 1];
+            rank += two.x > mine;
+            rank += two.y > mine;
+        }
+        if (inb[q] && rank < st.width) {
+            st.next_score[rank] = score[q];
+            st.next_token[rank] = (int)(unsigned)r[q];
+            st.next_hist[rank] = (int)(st.hist_offset + lane + kWave * q);
+        }
+    }
+}
+
+/*
  * A workgroup merges the G <= 256 mailbox records of rows first, first + stride, ... of H,
  * k <= 16.  Four wavefronts (one per SIMD; the others only keep the barriers company)
  * fetch, and keep fetching until none is empty: entry t of all G lists for the list
@@ -784,7 +859,8 @@ __device__ __noinline__ void final_merge_general(Partials P, int G, int first, i
  */
 __device__ __forceinline__ void merge_rows_mailbox(const Mailbox &mb, const Partials &P, unsigned *error, int G,
                                                    int first, int stride, int M, int k, int *token_ids,
-                                                   float *logp, MergeScratch *ms, SelectScratch *sc) {
+                                                   float *logp, MergeScratch *ms, SelectScratch *sc,
+                                                   unsigned long long *step_rec) {
     constexpr int HPL = 4;                      // G <= 256
     constexpr int NW = 4;                       // fetching wavefronts
     constexpr int TPW = kMailK / NW;            // list positions per fetching wavefront
@@ -928,12 +1004,16 @@ __device__ __forceinline__ void merge_rows_mailbox(const Mailbox &mb, const Part
                     rank += two.y > mine;
                 }
                 if (mine != 0ull && rank < k) {
-                    token_ids[(size_t)m * k + rank] = (int)~(unsigned)mine;
-                    logp[(size_t)m * k + rank] = value_of_key_hi((unsigned)(mine >> 32)) - logZ;
+                    const int tok = (int)~(unsigned)mine;
+                    const float lp = value_of_key_hi((unsigned)(mine >> 32)) - logZ;
+                    token_ids[(size_t)m * k + rank] = tok;
+                    logp[(size_t)m * k + rank] = lp;
+                    if (step_rec) publish(step_rec + m * kMailK + rank, mail_pack(lp, (unsigned)tok));
                 }
                 if (lane >= n && lane < k) {   // fewer candidates than k in the whole subset
                     token_ids[(size_t)m * k + lane] = INT_MAX;
                     logp[(size_t)m * k + lane] = kNegInf;
+                    if (step_rec) publish(step_rec + m * kMailK + lane, mail_pack(kNegInf, (unsigned)INT_MAX));
                 }
                 empty_my_records();
             }
@@ -963,7 +1043,16 @@ __device__ __forceinline__ void merge_rows_mailbox(const Mailbox &mb, const Part
             }
             wait_stores_done();
             __syncthreads();
-            if (wave == 0) final_merge_general(P, G, m, M, M, k, token_ids, logp, sc);   // this row only
+            if (wave == 0) {
+                final_merge_general(P, G, m, M, M, k, token_ids, logp, sc);   // this row only
+                if (step_rec) {   // hand the row on from where the general merge wrote it
+                    wait_stores_done();
+                    if (lane < k)
+                        publish(step_rec + m * kMailK + lane,
+                                mail_pack(observe(logp + (size_t)m * k + lane),
+                                          (unsigned)observe(token_ids + (size_t)m * k + lane)));
+                }
+            }
         }
     }
 }

@@ -22,12 +22,30 @@ struct WorkspaceView {
     unsigned *ticket;
     unsigned long long *mail_rec;   // self-validating records of the skinny kernel
     unsigned long long *mail_st;
+    unsigned long long *step_rec;   // hand-over records of the fused beam-search expansion
     float *part_ms;
     float *part_val;
     int *part_id;
 };
 
+// Arguments of the beam-search expansion that can ride on the skinny kernel's launch (see
+// expand_step_fused): the nodes of the step, the search history, the next nodes.
+struct StepArgs {
+    unsigned long long *rec;   // [kMailRows][kMailK]; nullptr: no expansion in this launch
+    const float *node_score;
+    const int *node_hist;
+    int width;
+    long long hist_offset;
+    float *hist_score;
+    int *hist_token;
+    int *hist_parent;
+    float *next_score;
+    int *next_token;
+    int *next_hist;
+};
+
 struct HeadProblem {
+    const StepArgs *step;   // optional: beam-search expansion fused into the launch (skinny kernel)
     const void *H;        // bf16 [M, d]; or, with scattered_rows, row m starts row_delta[m] bytes from H
     bool scattered_rows;  // (skinny kernel only, M <= 16)
     long long row_delta[16];
@@ -47,6 +65,7 @@ constexpr size_t kWorkspaceHeaderBytes = 512;
 // x 512 workgroups, 8 bytes each, all ones while empty.
 constexpr size_t kMailRecBytes = 16u * 16u * 512u * 8u;
 constexpr size_t kMailStBytes = 16u * 512u * 8u;
+constexpr size_t kStepRecBytes = 16u * 16u * 8u;   // one record per (row of H, list position)
 constexpr int kWorkspaceGridMax = 512;   // partial slots reserved per row of H
 constexpr int kMatrixPathMaxM = 256;     // rows of H per matrix-core launch
 constexpr int kSkinnyMaxM = 16;          // rows of H the vector-ALU kernel covers

@@ -64,6 +64,7 @@ struct SkinnyArgs {
     int sink;
     Partials part;
     Mailbox mail;
+    StepArgs step;
     unsigned *ticket;
     int *token_ids;
     float *logp;
@@ -455,7 +456,10 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
         if (b % spread != 0 || b / spread >= R) return;
         stamp(4);
         merge_rows_mailbox(a.mail, part, a.ticket + 1, G, b / spread, R, a.M, a.k, a.token_ids, a.logp, &s_merge,
-                           &s_select[0]);
+                           &s_select[0], a.step.rec);
+        // the first merger also runs the beam-search expansion of the step, if one was asked for
+        if (a.step.rec && b == 0 && wave == 0)
+            expand_step_fused(a.step, a.M, a.k, reinterpret_cast<unsigned long long *>(s_select), a.ticket + 1);
     } else {
         const int r = arrive_and_wait(ar, (unsigned)__builtin_amdgcn_readfirstlane((int)turn), G, R, &s_slot);
         stamp(4);
@@ -626,6 +630,13 @@ fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hip
     a.ticket = p.ws.ticket;
     a.mail.rec = p.ws.mail_rec;
     a.mail.st = p.ws.mail_st;
+    if (p.step) {
+        // the expansion rides on the mailbox merge: k <= 16, one launch, at most 256 workgroups
+        if (sink != Sink::kFusedTopk || p.k > kSmallKMax || cus > 4 * kWave || p.M * p.k > kMailRows * kMailK)
+            return FR_ERR_UNSUPPORTED;
+        a.step = *p.step;
+        a.step.rec = p.ws.step_rec;
+    }
     a.token_ids = p.token_ids;
     a.logp = p.logp;
     a.z_out = p.z_out;

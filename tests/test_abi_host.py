@@ -169,3 +169,17 @@ def test_token_statistics_reject_bad_arguments():
     assert L.fr_rank_tokens(0, 100, 0x2000, None) == INVALID
     assert L.fr_rank_tokens(0x1000, 0, 0x2000, None) == INVALID
     assert L.fr_rank_tokens(0x1000, (1 << 22) + 1, 0x2000, None) == UNSUPPORTED
+
+
+def test_draft_step_rejects_bad_arguments_before_any_launch():
+    L = fr.lib()
+    P = [0x1000 * (i + 1) for i in range(16)]
+
+    def step(H=P[0], M=10, d=4096, W=P[1], V=32768, k=10, ns=P[2], nh=P[3], width=10, hs=P[4], ht=P[5], hp=P[6],
+             off=0, ids=P[7], lp=P[8], os_=P[9], ot=P[10], oh=P[11], ws=P[12]):
+        return L.fr_draft_step(H, M, d, W, 0, V, k, ns, nh, width, hs, ht, hp, off, ids, lp, os_, ot, oh, ws,
+                               1 << 26, None)
+
+    assert step(ns=0) == INVALID and step(oh=0) == INVALID and step(hs=0) == INVALID
+    assert step(width=0) == INVALID and step(width=101) == INVALID and step(off=-1) == INVALID
+    assert step(H=0) == INVALID and step(k=0) == INVALID and step(ids=0) == INVALID

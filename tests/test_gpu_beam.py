@@ -112,3 +112,72 @@ def test_six_step_draft_with_the_lm_head_in_the_loop():
         assert np.array_equal(g.cpu().numpy(), w)
     assert (want[2] != -2).all()            # every selected entry has its parent selected
     assert int(want[3].max()) <= depth - 1
+
+
+@pytest.mark.parametrize("M,k,width,V_sub,off", [(1, 10, 10, 2048, 0), (10, 10, 10, 2048, 10), (16, 16, 50, 3000, 7),
+                                                 (10, 10, 100, 300, 0), (4, 4, 3, 64, 5),
+                                                 (10, 20, 10, 2048, 0), (20, 10, 10, 2048, 0)])
+def test_fused_draft_step_equals_the_two_calls(M, k, width, V_sub, off):
+    # fr_draft_step = fr_draft_topk + fr_beam_expand; for M <= 16, k <= 16 inside one launch.
+    # The fused path sees the same log-probabilities, so everything must agree bit for bit; the
+    # two calls themselves are checked against the oracle elsewhere.
+    from parity_utils import to_dev_bf16, to_dev_i32
+    from synth import make_hidden, make_weights, zipf_ranking
+    _say("fused draft step", M, k, width, V_sub, off)
+    d, V = 256, 8192
+    W = make_weights(V, d, 2)
+    r, _ = zipf_ranking(V, 1.1, 10 ** 6, 2)
+    W_g, idx_g = fr.fr_build_subset(to_dev_bf16(W), to_dev_i32(r), V_sub)
+    ws = fr.new_workspace(M, d, V, k)
+    rng = np.random.default_rng([20250214, 101, M, k])
+    node_score = _dev((-rng.integers(0, 8, size=M) / 2).astype(np.float32))
+    node_hist = _dev(rng.integers(-1, max(off, 1), size=M).astype(np.int32))
+    n = off + M * k
+    for rep in range(2):       # twice on one workspace: the hand-over records must be empty again
+        H = to_dev_bf16(make_hidden(M, d, 200 + rep))
+        hist_a = [_dev(np.full(n, 7.0, np.float32)), _dev(np.full(n, 7, np.int32)), _dev(np.full(n, 7, np.int32))]
+        hist_b = [t.clone() for t in hist_a]
+        ids_a, lp_a = fr.fr_draft_topk(H, W_g, idx_g, k, ws)
+        nxt_a = fr.fr_beam_expand(lp_a, ids_a, node_score, node_hist, width, *hist_a, off)
+        ids_b, lp_b, *nxt_b = fr.fr_draft_step(H, W_g, idx_g, k, node_score, node_hist, width, *hist_b, off, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(ids_b.cpu().numpy(), ids_a.cpu().numpy())
+        assert np.array_equal(_bits(lp_b.cpu().numpy()), _bits(lp_a.cpu().numpy()))
+        for x, y in zip(hist_a + list(nxt_a), hist_b + list(nxt_b)):
+            xa, ya = x.cpu().numpy(), y.cpu().numpy()
+            assert np.array_equal(xa.view(np.uint32), ya.view(np.uint32))
+        step_region = ws[512 + (16 * 16 + 16) * 512 * 8:][:16 * 16 * 8].cpu().numpy()
+        assert (step_region == 0xFF).all()
+    assert fr.fr_workspace_check(ws) is False
+
+
+def test_six_fused_steps_equal_six_unfused_steps():
+    from parity_utils import to_dev_bf16, to_dev_i32
+    from synth import make_hidden, make_weights, zipf_ranking
+    d, V, V_sub, k, width, depth, K = 256, 8192, 2048, 10, 10, 6, 60
+    W = make_weights(V, d, 0)
+    r, _ = zipf_ranking(V, 1.1, 10 ** 6, 0)
+    W_g, idx_g = fr.fr_build_subset(to_dev_bf16(W), to_dev_i32(r), V_sub)
+    ws = fr.new_workspace(width, d, V, k)
+    cap = k + (depth - 1) * width * k
+    out = []
+    for fused in (False, True):
+        hist = [torch.zeros(cap, dtype=torch.float32, device="cuda"), torch.zeros(cap, dtype=torch.int32, device="cuda"),
+                torch.zeros(cap, dtype=torch.int32, device="cuda")]
+        ns = torch.zeros(1, dtype=torch.float32, device="cuda")
+        nh = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+        off = 0
+        for step in range(depth):
+            M = ns.numel()
+            H = to_dev_bf16(make_hidden(M, d, 100 + step))
+            if fused:
+                _, _, ns, _, nh = fr.fr_draft_step(H, W_g, idx_g, k, ns, nh, min(width, M * k), *hist, off, ws)
+            else:
+                ids, lp = fr.fr_draft_topk(H, W_g, idx_g, k, ws)
+                ns, _, nh = fr.fr_beam_expand(lp, ids, ns, nh, min(width, M * k), *hist, off)
+            off += M * k
+        sel = fr.fr_tree_select(*hist, off, K)
+        torch.cuda.synchronize()
+        out.append([t.cpu().numpy() for t in hist + list(sel)])
+    for a, b in zip(*out):
+        assert np.array_equal(a.view(np.uint8), b.view(np.uint8))
