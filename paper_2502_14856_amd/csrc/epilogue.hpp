@@ -2,10 +2,17 @@
 //
 // A workgroup owns a set of vocabulary rows.  For every row m of H it keeps, in LDS,
 //   run_ms[m]  = (mx, S): running maximum of its logits and sum of exp(z - mx),
-//   run_val/run_id[m][0..k): its k best (logit, token id) pairs, best first.
-// At the end these go to the workspace; one wavefront per row m then merges the G
-// workgroups' partials into log Z (Eq. 4's normaliser over the subset), the final k
-// candidates, and writes token ids and log-probabilities.
+//   run_val/run_id[m][0..k): its k best (logit, token id) pairs, best first,
+// folded pass by pass (fold_pass).  On the workgroup's last pass the state goes to the
+// workspace, where a few workgroups of the same launch merge the G partial results of every
+// row into log Z (Eq. 4's normaliser over the subset) and the final k candidates, and write
+// token ids and log-probabilities.  Two ways to the workspace and back:
+//   * k <= 16, G <= 256, skinny kernel: self-validating mailbox records, merged by
+//     merge_rows_mailbox (and, on request, expanded by expand_step_fused);
+//   * otherwise: plain partial arrays plus an arrival counter (arrive_and_wait), merged by
+//     final_merge_all, in the same launch or in a second one.
+// fold_pair_fast / merge_rows_mailbox are the fast paths; block_fold_rows / final_merge_rows
+// are the general ones (any k, any number of tied values).
 #pragma once
 
 #include "internal.hpp"
@@ -259,23 +266,6 @@ __device__ __forceinline__ void block_fold_rows(const FoldRow (&row)[NS], int KS
     }
 }
 
-// Folds rows m = first, first + stride, ... < M of H, two at a time where possible.
-template <int ZR, bool WITH_RUN, typename RowOf>
-__device__ __forceinline__ void block_fold_all(int first, int stride, int M, RowOf row_of, int KS,
-                                               int z_slice_stride, const int *ids_pass, int n_valid,
-                                               int k, SelectScratch *sc) {
-    int m = first;
-    for (; m + stride < M; m += 2 * stride) {
-        const FoldRow rows[2] = {row_of(m), row_of(m + stride)};
-        block_fold_rows<ZR, 2, WITH_RUN>(rows, KS, z_slice_stride, ids_pass, n_valid, k, sc);
-    }
-    if (m < M) {
-        const FoldRow rows[1] = {row_of(m)};
-        block_fold_rows<ZR, 1, WITH_RUN>(rows, KS, z_slice_stride, ids_pass, n_valid, k, sc);
-    }
-}
-
-
 // ---------------------------------------------------------------------------------------
 // Fast paths for k <= kSmallKMax (16).  Both rest on the same bound: split the candidates
 // into 16 groups; the k-th largest of the 16 group maxima is a lower bound of the k-th best
@@ -522,12 +512,6 @@ __device__ __forceinline__ void fold_pass(const float *z_lds, int z_row_stride, 
     }
 }
 
-#ifdef FRSPEC_MERGE_TRACE
-#define FRSPEC_MERGE_STAMP(i) \
-    do { if (lane_id() == 0) FRSPEC_MERGE_TRACE[i] = (long long)__builtin_readcyclecounter(); } while (0)
-#else
-#define FRSPEC_MERGE_STAMP(i) do { } while (0)
-#endif
 
 // Candidate number c of the triangle {(i, t): i + t < k}, rows i listed one after the
 // other (row i holds k - i entries and starts at i*k - i(i-1)/2).
@@ -553,7 +537,6 @@ template <int NS, int HPL>
 __device__ __forceinline__ void final_merge_rows(const Partials &P, int G, const int (&m)[NS], int k,
                                                  int *token_ids, float *logp, SelectScratch *sc) {
     const int lane = lane_id();
-    FRSPEC_MERGE_STAMP(0);
     float hv[NS][HPL];
     int hid[NS][HPL], hg[NS][HPL];
     float logZ[NS];
@@ -589,7 +572,6 @@ __device__ __forceinline__ void final_merge_rows(const Partials &P, int G, const
     }
 
     const int n_cand = k * (k + 1) / 2;
-    FRSPEC_MERGE_STAMP(1);
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
         // ---- the k lists with the best heads: sc->pl[i] = workgroup of list number i
@@ -621,7 +603,6 @@ __device__ __forceinline__ void final_merge_rows(const Partials &P, int G, const
             wave_select_topk<1, HPL>(v1, id1, pl1, k, lv, lid, lg1);
             if (lane < k) sc->pl[lane] = lg1[0];
         }
-        FRSPEC_MERGE_STAMP(2);
 
         // ---- candidates (i, t), i + t < k
         auto fetch = [&](int c, float &cv, int &cid) {
@@ -641,7 +622,6 @@ __device__ __forceinline__ void final_merge_rows(const Partials &P, int G, const
                 float cv;
                 int cid;
                 fetch(lane, cv, cid);
-                FRSPEC_MERGE_STAMP(3);
                 const unsigned long long mine =
                     cid != INT_MAX ? make_key(key_hi_of(cv), ~(unsigned)cid) : 0ull;
                 const int rank = wave_rank_all(mine, sc);
@@ -660,7 +640,6 @@ __device__ __forceinline__ void final_merge_rows(const Partials &P, int G, const
                 int cid[C2], cpl[C2];
 #pragma unroll
                 for (int q = 0; q < C2; ++q) fetch(lane + kWave * q, cv[q], cid[q]);
-                FRSPEC_MERGE_STAMP(3);
                 unsigned hi[C2], lo[C2];
 #pragma unroll
                 for (int q = 0; q < C2; ++q) {
@@ -730,7 +709,6 @@ __device__ __forceinline__ void final_merge_rows(const Partials &P, int G, const
                 logp[(size_t)m[s] * k + lane] = ov - logZ[s];
             }
         }
-        FRSPEC_MERGE_STAMP(4);
     }
 }
 

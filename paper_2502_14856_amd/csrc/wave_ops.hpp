@@ -196,12 +196,6 @@ constexpr int kSmallKMax = 16;   // largest k the threshold selection handles
  * candidates survive (massively tied values): the caller then falls back to the
  * round-by-round selection.
  */
-#ifdef FRSPEC_SELECT_TRACE
-#define FRSPEC_SELECT_STAMP(i) \
-    do { if (lane_id() == 0) FRSPEC_SELECT_TRACE[i] = (long long)__builtin_readcyclecounter(); } while (0)
-#else
-#define FRSPEC_SELECT_STAMP(i) do { } while (0)
-#endif
 
 template <int CPL>
 __device__ __forceinline__ bool wave_topk_small(const unsigned (&hi)[CPL], const unsigned (&lo)[CPL],
@@ -209,7 +203,6 @@ __device__ __forceinline__ bool wave_topk_small(const unsigned (&hi)[CPL], const
                                                 unsigned long long &mine, int &mine_pl, int &rank,
                                                 int &n) {
     const int lane = lane_id();
-    FRSPEC_SELECT_STAMP(0);
     unsigned qm = hi[0];
 #pragma unroll
     for (int c = 1; c < CPL; ++c) qm = max(qm, hi[c]);
@@ -219,9 +212,7 @@ __device__ __forceinline__ bool wave_topk_small(const unsigned (&hi)[CPL], const
 #pragma unroll
     for (int q = 0; q < 16; ++q) greater += (unsigned)__builtin_amdgcn_readlane((int)qm, 4 * q) > qm;
     // the smallest quad maximum that still is among the k largest = the k-th largest
-    FRSPEC_SELECT_STAMP(1);
     const unsigned L = wave_min_u32(greater <= k - 1 ? qm : 0xFFFFFFFFu);
-    FRSPEC_SELECT_STAMP(2);
 
     n = 0;
 #pragma unroll
@@ -236,18 +227,15 @@ __device__ __forceinline__ bool wave_topk_small(const unsigned (&hi)[CPL], const
         }
         n += (int)__popcll(mask);
     }
-    FRSPEC_SELECT_STAMP(3);
     if (n > kWave) return false;
 
     mine = lane < n ? sc->key[lane] : 0ull;
     mine_pl = lane < n ? sc->pl[lane] : -1;
     rank = 0;
-    FRSPEC_SELECT_STAMP(4);
     // every survivor is compared with every survivor; the keys are read back from LDS
     // (same address in all lanes: a broadcast), several reads in flight at a time
 #pragma unroll 8
     for (int j = 0; j < n; ++j) rank += sc->key[j] > mine;
-    FRSPEC_SELECT_STAMP(5);
     return true;
 }
 
