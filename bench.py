@@ -135,6 +135,15 @@ def main() -> int:
     # ---- context measurements ----
     t_warm = timed(lambda i: fr.fr_draft_topk(H, copies[0], idx_map, k, ws, token_ids=ids, logp=logp),
                    max(50, args.steps // 4), 20)
+    # per-call latency: one pair of events around every call of a second cold rotation
+    n_lat = 300
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_lat)]
+    for i, (a, b) in enumerate(pairs):
+        a.record()
+        step(i)
+        b.record()
+    torch.cuda.synchronize()
+    lat_us = np.sort(np.array([a.elapsed_time(b) for a, b in pairs])) * 1e3
     ids_f = torch.empty((M, k), dtype=torch.int32, device="cuda")
     lp_f = torch.empty((M, k), dtype=torch.float32, device="cuda")
     t_full = timed(lambda i: fr.fr_full_topk(H, W_full, k, ws, token_ids=ids_f, logp=lp_f),
@@ -246,6 +255,10 @@ def main() -> int:
         "extra": {
             "us_per_call_cold": t_step * 1e6,
             "us_per_call_same_buffer": t_warm * 1e6,
+            "us_per_call_same_buffer_note": "MALL-assisted: the same 256 MiB every call",
+            "latency_us_p50": float(lat_us[n_lat // 2]),
+            "latency_us_p99": float(lat_us[(n_lat * 99) // 100]),
+            "latency_note": "one event pair per call, cold rotation; includes the events' own gaps",
             "full_topk_us_per_call": t_full * 1e6,
             "full_topk_calls_per_s": 1.0 / t_full,
             "full_topk_gbps": V * d * 2 / t_full / 1e9,

@@ -223,9 +223,10 @@ typedef struct fr_tuning {
                             (no softmax, no top-k; token_ids / logp are left untouched) */
     int32_t skew;        /* > 0: rows that every odd workgroup hands to its even neighbour when each
                             workgroup has exactly one pass (experimental die balancing; off by default) */
-    int32_t reserved1;
-    void *trace;         /* optional device buffer of 8 * 512 int64: every workgroup of the
-                            skinny kernel records 100 MHz timestamps of its phases there */
+    int32_t no_mailbox;  /* 1 = the chunked kernel merges through the plain partial arrays and the
+                            arrival counter even where the result mailbox applies */
+    void *trace;         /* optional device buffer of 8 * 512 int64: every workgroup of a
+                            contraction kernel records 100 MHz timestamps of its phases there */
 } fr_tuning;
 
 /* fr_draft_topk with explicit knobs (tuning == NULL behaves exactly like fr_draft_topk). */

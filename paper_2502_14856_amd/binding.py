@@ -29,7 +29,7 @@ class Tuning(ctypes.Structure):
     _fields_ = [("path", ctypes.c_int32), ("two_launch", ctypes.c_int32),
                 ("variant", ctypes.c_int32), ("ksplit", ctypes.c_int32),
                 ("grid", ctypes.c_int32), ("stream_only", ctypes.c_int32),
-                ("skew", ctypes.c_int32), ("reserved1", ctypes.c_int32),
+                ("skew", ctypes.c_int32), ("no_mailbox", ctypes.c_int32),
                 ("trace", ctypes.c_void_p)]
 
 

@@ -65,7 +65,8 @@ struct Mailbox {
     unsigned long long *rec;
     unsigned long long *st;
 };
-constexpr int kMailRows = 16, kMailK = 16;
+constexpr int kMailRows = 64, kMailK = 16;   // rows of H and list positions with records
+constexpr int kStepRows = 16;                 // rows of H whose results the fused expansion collects
 constexpr unsigned long long kMailEmpty = ~0ull;
 constexpr unsigned kMailSpinLimit = 1u << 20;   // rounds of about a microsecond before giving up
 __device__ __forceinline__ size_t mail_rec_index(int m, int t, int g) {
@@ -283,8 +284,12 @@ typedef unsigned long long u64x2 __attribute__((ext_vector_type(2)));
 // C consecutive 4-byte words of LDS, as one access.
 template <int C, typename T, typename V4, typename V2>
 __device__ __forceinline__ void lds_words(const T *p, T (&out)[C]) {
-    static_assert(C == 1 || C == 2 || C == 4, "1, 2 or 4 words per lane");
-    if constexpr (C == 4) {
+    static_assert(C == 1 || C == 2 || C == 4 || C == 8, "1, 2, 4 or 8 words per lane");
+    if constexpr (C == 8) {
+        const V4 a = *reinterpret_cast<const V4 *>(p), b = *reinterpret_cast<const V4 *>(p + 4);
+        out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
+        out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
+    } else if constexpr (C == 4) {
         const V4 v = *reinterpret_cast<const V4 *>(p);
         out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
     } else if constexpr (C == 2) {
@@ -466,6 +471,118 @@ __device__ __forceinline__ bool fold_pair_fast(const float *z_lds, int z_row_str
     return true;
 }
 
+/*
+ * The same for FOUR rows of H at once, one per quarter of the wavefront (a DPP row of 16
+ * lanes): lane (r, l16) works on row `m` (the same for the 16 lanes of a quarter) and holds
+ * C = ZR_MAX / 16 consecutive local vocabulary rows, plus entry l16 of the row's running
+ * list when WITH_RUN.  A group is one lane, so the 16 group maxima already sit in the 16
+ * lanes of the row.  Up to 32 survivors per row, two per lane when they are ranked.
+ */
+template <int ZR_MAX, bool WITH_RUN>
+__device__ __forceinline__ bool fold_quad_fast(const float *z_lds, int z_row_stride, int m_base, int KS,
+                                               int z_slice_stride, const int *ids_pass, int n_valid, int k, int m,
+                                               bool active, const FoldSink &out, SelectScratch *sc) {
+    constexpr int C = ZR_MAX / 16;
+    constexpr int CPL = C + (WITH_RUN ? 1 : 0);
+    const int lane = lane_id(), r = lane >> 4, l16 = lane & 15;
+    const int mm = active ? m : m_base;
+
+    float z[C];
+#pragma unroll
+    for (int c = 0; c < C; ++c) z[c] = 0.0f;
+    const float *zp = z_lds + (mm - m_base) * z_row_stride + l16 * C;
+    for (int q = 0; q < KS; ++q) {
+        float t[C];
+        lds_words<C, float, fvec4, fvec2>(zp + q * z_slice_stride, t);
+#pragma unroll
+        for (int c = 0; c < C; ++c) z[c] += t[c];
+    }
+    int id[C];
+    lds_words<C, int, ivec4, ivec2>(ids_pass + l16 * C, id);
+    const int kk = l16 < k ? l16 : k - 1;
+    float old_mx = kNegInf, old_S = 0.0f, run_v = kNegInf;
+    int run_i = INT_MAX;
+    if (WITH_RUN) {
+        old_mx = out.run_ms[2 * mm];
+        old_S = out.run_ms[2 * mm + 1];
+        run_v = out.run_val[mm * k + kk];
+        run_i = out.run_id[mm * k + kk];
+        if (!(active && l16 < k)) run_i = INT_MAX;
+    }
+
+    // online softmax statistics of the row (Eq. 4's normaliser, accumulated per pass)
+    float v[C];
+    bool ok[C];
+    float lmax = kNegInf;
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+        ok[c] = active && (l16 * C + c < n_valid);
+        v[c] = ok[c] ? z[c] : kNegInf;
+        lmax = fmaxf(lmax, v[c]);
+    }
+    const float mx = fmaxf(old_mx, row16_max_f32(lmax));
+    float part = 0.0f;
+#pragma unroll
+    for (int c = 0; c < C; ++c) part += exp_diff(v[c], mx);
+    const float S = old_S * exp_diff(old_mx, mx) + row16_sum_all(part);
+
+    // candidates as keys, and the bound: the k-th largest of the 16 lane maxima
+    unsigned hi[CPL], lo[CPL];
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+        hi[c] = ok[c] ? key_hi_of(v[c]) : 0u;
+        lo[c] = ~(unsigned)id[c];
+    }
+    if (WITH_RUN) {
+        hi[CPL - 1] = run_i != INT_MAX ? key_hi_of(run_v) : 0u;
+        lo[CPL - 1] = ~(unsigned)run_i;
+    }
+    unsigned lm = hi[0];
+#pragma unroll
+    for (int c = 1; c < CPL; ++c) lm = max(lm, hi[c]);
+    const unsigned L = row16_kth_largest_u32(lm, k);
+
+    // survivors of each row, packed into its 32 scratch slots
+    sc->key[lane] = 0ull;
+    sc->key[kWave + lane] = 0ull;
+    const unsigned below = (1u << l16) - 1u;
+    int n = 0;   // survivors of this lane's row so far
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+        const bool sv = hi[c] != 0u && hi[c] >= L;
+        const unsigned field = (unsigned)(__ballot(sv) >> (16 * r)) & 0xFFFFu;
+        const int pos = n + __popc(field & below);
+        if (sv && pos < 32) sc->key[r * 32 + pos] = make_key(hi[c], lo[c]);
+        n += __popc(field);
+    }
+    if (__any(n > 32)) return false;
+
+    // rank = number of better survivors of the same row (the unused slots hold zero keys);
+    // lane l16 ranks the survivors in slots l16 and 16 + l16
+    const unsigned long long mine_a = sc->key[r * 32 + l16], mine_b = sc->key[r * 32 + 16 + l16];
+    const u64x2 *kp = reinterpret_cast<const u64x2 *>(sc->key + r * 32);
+    const int nmax = max(max(__builtin_amdgcn_readlane(n, 0), __builtin_amdgcn_readlane(n, 16)),
+                         max(__builtin_amdgcn_readlane(n, 32), __builtin_amdgcn_readlane(n, 48)));
+    int rank_a = 0, rank_b = 0;
+#pragma unroll 4
+    for (int j = 0; j < nmax; j += 2) {
+        const u64x2 two = kp[j >> 1];
+        rank_a += two.x > mine_a;
+        rank_a += two.y > mine_a;
+        rank_b += two.x > mine_b;
+        rank_b += two.y > mine_b;
+    }
+    if (active) {
+        if (mine_a != 0ull && rank_a < k)
+            out.entry(m, k, rank_a, value_of_key_hi((unsigned)(mine_a >> 32)), (int)~(unsigned)mine_a);
+        if (mine_b != 0ull && rank_b < k)
+            out.entry(m, k, rank_b, value_of_key_hi((unsigned)(mine_b >> 32)), (int)~(unsigned)mine_b);
+        if (l16 >= n && l16 < k) out.entry(m, k, l16, kNegInf, INT_MAX);   // fewer candidates than k
+        if (l16 == 0) out.stats(m, mx, S);
+    }
+    return true;
+}
+
 // General fold of one row by one whole wavefront, kept out of line: any k, any number of
 // tied values.  The row's state stays in LDS; on the workgroup's last pass it is also
 // written out.
@@ -483,17 +600,33 @@ __device__ __noinline__ void fold_row_general(FoldRow row, int KS, int z_slice_s
 
 /*
  * Folds one pass into the running state of rows m_base <= m < m_end of H, or, on the
- * workgroup's last pass, writes the result out (see FoldSink).  Wavefront w of `waves` takes
- * rows m_base + w and m_base + w + waves (then + 2 * waves, ...), two at a time in its two
- * halves while k <= 16.
+ * workgroup's last pass, writes the result out (see FoldSink).  While k <= 16, wavefront w
+ * of `waves` takes rows m_base + w and m_base + w + waves (then + 2 * waves, ...), two at a
+ * time in its two halves; with QUAD, rows m_base + 4w .. 4w + 3 (then + 4 * waves, ...), four
+ * at a time in its quarters.  A fold is one long chain of dependent instructions and LDS
+ * round trips, and the four-row one is the longer chain: QUAD pays off where the rows
+ * would otherwise take more than one round per wavefront.
  */
-template <int ZR_MAX, bool WITH_RUN, bool WITH_EXTRA = false, typename RowOf>
+template <int ZR_MAX, bool WITH_RUN, bool WITH_EXTRA = false, bool QUAD = false, typename RowOf>
 __device__ __forceinline__ void fold_pass(const float *z_lds, int z_row_stride, int KS, int z_slice_stride,
                                           const int *ids_pass, int n_valid, int k, int m_base, int m_end, int wave,
                                           int waves, RowOf row_of, const FoldSink &out, SelectScratch *sc) {
     // the general fold covers 64 local rows per lane slot: one more slot takes the extra rows
     constexpr int ZR_GEN = WITH_EXTRA ? ZR_MAX + kWave : ZR_MAX;
-    if (k <= kSmallKMax) {
+    static_assert(!(QUAD && WITH_EXTRA), "the four-row fold takes no extra rows");
+    if (QUAD && k <= kSmallKMax) {
+        for (int mb = m_base; mb < m_end; mb += 4 * waves) {
+            const int m0 = mb + 4 * wave;
+            if (m0 >= m_end) break;
+            const int m = m0 + (lane_id() >> 4);
+            if (fold_quad_fast<ZR_MAX, WITH_RUN>(z_lds, z_row_stride, m_base, KS, z_slice_stride, ids_pass, n_valid, k,
+                                                 m, m < m_end, out, sc))
+                continue;
+            for (int i = 0; i < 4 && m0 + i < m_end; ++i)
+                fold_row_general<ZR_GEN, WITH_RUN>(row_of(m0 + i), KS, z_slice_stride, ids_pass, n_valid, k, sc, out,
+                                                   m0 + i);
+        }
+    } else if (k <= kSmallKMax) {
         for (int mb = m_base; mb < m_end; mb += 2 * waves) {
             const int m_lo = mb + wave, m_hi = mb + wave + waves;
             if (m_lo >= m_end) break;
@@ -762,7 +895,7 @@ __device__ __noinline__ void final_merge_general(Partials P, int G, int first, i
 // One wavefront; keys: LDS, at least M * k + 2 entries, 16-byte aligned.
 __device__ __forceinline__ void expand_step_fused(const StepArgs &st, int M, int k, unsigned long long *keys,
                                                   unsigned *error) {
-    constexpr int CPL = kMailRows * kMailK / kWave;   // 4 candidates per lane at most
+    constexpr int CPL = kStepRows * kMailK / kWave;   // 4 candidates per lane at most
     const int lane = lane_id(), C = M * k;
     unsigned long long r[CPL];
     int row[CPL], at[CPL];

@@ -20,7 +20,7 @@ enum class Sink : int {
 // Device-side view of the workspace.
 struct WorkspaceView {
     unsigned *ticket;
-    unsigned long long *mail_rec;   // self-validating records of the skinny kernel
+    unsigned long long *mail_rec;   // self-validating result records (single-launch merge)
     unsigned long long *mail_st;
     unsigned long long *step_rec;   // hand-over records of the fused beam-search expansion
     float *part_ms;
@@ -31,7 +31,7 @@ struct WorkspaceView {
 // Arguments of the beam-search expansion that can ride on the skinny kernel's launch (see
 // expand_step_fused): the nodes of the step, the search history, the next nodes.
 struct StepArgs {
-    unsigned long long *rec;   // [kMailRows][kMailK]; nullptr: no expansion in this launch
+    unsigned long long *rec;   // [16][16]; nullptr: no expansion in this launch
     const float *node_score;
     const int *node_hist;
     int width;
@@ -61,10 +61,10 @@ struct HeadProblem {
 };
 
 constexpr size_t kWorkspaceHeaderBytes = 512;
-// Mailbox of the skinny kernel: 16 rows of H x (16 list positions + 1 statistics record)
-// x 512 workgroups, 8 bytes each, all ones while empty.
-constexpr size_t kMailRecBytes = 16u * 16u * 512u * 8u;
-constexpr size_t kMailStBytes = 16u * 512u * 8u;
+// Result mailbox of the single-launch merge: 64 rows of H x (16 list positions + 1
+// statistics record) x 512 workgroups, 8 bytes each, all ones while empty.
+constexpr size_t kMailRecBytes = 64u * 16u * 512u * 8u;
+constexpr size_t kMailStBytes = 64u * 512u * 8u;
 constexpr size_t kStepRecBytes = 16u * 16u * 8u;   // one record per (row of H, list position)
 constexpr int kWorkspaceGridMax = 512;   // partial slots reserved per row of H
 constexpr int kMatrixPathMaxM = 256;     // rows of H per matrix-core launch

@@ -42,11 +42,14 @@ struct WideArgs {
     int passes;
     int sink;
     Partials part;
+    Mailbox mail;
+    int mailbox;  // the results go through the mailbox records (single launch, k <= 16, M <= 64)
     unsigned *ticket;
     int *token_ids;
     float *logp;
     float *z_out;
     int z_ld;
+    long long *trace;   // optional [gridDim.x][8] phase timestamps (100 MHz clock)
 };
 
 __host__ __device__ constexpr int wide_round_up(int x, int m) { return (x + m - 1) / m * m; }
@@ -89,6 +92,7 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
     int *run_id = reinterpret_cast<int *>(base + L.id_off);
     __shared__ int s_slot;
     __shared__ SelectScratch s_select[WAVES];
+    __shared__ MergeScratch s_merge;
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -96,6 +100,10 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
     const int lk = lane & 15, rs = lane >> 4;   // load layout: 16-byte chunk, row slot
     const int j = lk, g = rs;                   // operand layout: row / column, k group
     const int G = gridDim.x;
+    auto stamp = [&](int slot) {
+        if (a.trace && tid == 0) a.trace[blockIdx.x * 8 + slot] = (long long)__builtin_amdgcn_s_memrealtime();
+    };
+    stamp(0);
     // which arrival counter this call uses: asked for now, needed at the very end
     const Arrival ar(a.ticket);
     const unsigned turn = a.sink == (int)Sink::kFusedTopk ? ar.turn() : 0u;
@@ -265,9 +273,46 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
             }
         }
 
-        // ---- consume the pass, one tile of 16 H rows at a time ----
-        // (fully unrolled whatever its size: a rolled loop would index the accumulators
-        // dynamically and push them to scratch memory)
+        // ---- consume the pass ----
+        // While the logits of all Mp rows fit into the two H buffers (no longer needed once
+        // the products are done), they go there in one piece and every wavefront folds its
+        // rows of H without meeting the others again.
+        constexpr bool kAllAtOnce = 2 * HP * 16 >= (kZR + kZPad) * 4;
+        stamp(2);
+        if constexpr (kAllAtOnce) {
+            float *z_all = reinterpret_cast<float *>(H_lds);
+            __syncthreads();   // every wavefront is done with the H chunks
+#pragma clang loop unroll(full)
+            for (int mt = 0; mt < MT16; ++mt)
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb) {
+                    float *dst = z_all + (mt * 16 + j) * (kZR + kZPad) + (wave * RB + rb) * 16 + 4 * g;
+                    *reinterpret_cast<f32x4_t *>(dst) = acc[rb][mt];
+                }
+            __syncthreads();
+            if (a.sink == (int)Sink::kLogits) {
+                for (int e = tid; e < Mp * kZR; e += NT) {
+                    const int m = e / kZR, r = e - m * kZR;
+                    if (m < a.M && r < n_valid)
+                        a.z_out[(size_t)m * a.z_ld + pass_row0 + r] = z_all[m * (kZR + kZPad) + r];
+                }
+            } else if (a.sink != (int)Sink::kStreamOnly) {
+                auto row_of = [&](int m) {
+                    return FoldRow{z_all + m * (kZR + kZPad), run_ms + 2 * m, run_val + m * a.k, run_id + m * a.k};
+                };
+                const FoldSink out{FoldTo::kLds, Partials{}, Mailbox{}, 0, run_ms, run_val, run_id};
+                constexpr bool kQuad = Mp > 2 * WAVES;   // two rows per wavefront would take several rounds
+                if (p == (int)blockIdx.x)
+                    fold_pass<kZR, false, false, kQuad>(z_all, kZR + kZPad, 1, 0, ids_lds, n_valid, a.k, 0, a.M, wave,
+                                                        WAVES, row_of, out, &s_select[wave]);
+                else
+                    fold_pass<kZR, true, false, kQuad>(z_all, kZR + kZPad, 1, 0, ids_lds, n_valid, a.k, 0, a.M, wave,
+                                                       WAVES, row_of, out, &s_select[wave]);
+            }
+            continue;
+        }
+        // Otherwise one tile of 16 H rows at a time (fully unrolled whatever its size: a rolled
+        // loop would index the accumulators dynamically and push them to scratch memory).
 #pragma clang loop unroll(full)
         for (int mt = 0; mt < MT16; ++mt) {
             __syncthreads();   // z_stage is free (and, the first time, the last H chunk is done with)
@@ -292,12 +337,13 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
                 };
                 // the running state stays in LDS; it is written out once, after the last pass
                 const FoldSink out{FoldTo::kLds, Partials{}, Mailbox{}, 0, run_ms, run_val, run_id};
+                constexpr bool kQuad = 16 > 2 * WAVES;
                 if (p == (int)blockIdx.x)
-                    fold_pass<kZR, false>(z_stage, kZR + kZPad, 1, 0, ids_lds, n_valid, a.k, mt * 16, m_end, wave,
-                                          WAVES, row_of, out, &s_select[wave]);
+                    fold_pass<kZR, false, false, kQuad>(z_stage, kZR + kZPad, 1, 0, ids_lds, n_valid, a.k, mt * 16,
+                                                        m_end, wave, WAVES, row_of, out, &s_select[wave]);
                 else
-                    fold_pass<kZR, true>(z_stage, kZR + kZPad, 1, 0, ids_lds, n_valid, a.k, mt * 16, m_end, wave,
-                                         WAVES, row_of, out, &s_select[wave]);
+                    fold_pass<kZR, true, false, kQuad>(z_stage, kZR + kZPad, 1, 0, ids_lds, n_valid, a.k, mt * 16,
+                                                       m_end, wave, WAVES, row_of, out, &s_select[wave]);
             }
         }
     }
@@ -305,8 +351,30 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
     if (a.sink == (int)Sink::kLogits || a.sink == (int)Sink::kStreamOnly) return;
 
     __syncthreads();
+    stamp(3);
     const int gidx = blockIdx.x;
     const Partials part = a.part;   // a local copy keeps the argument block itself in registers
+    if (a.mailbox) {
+        // Every row's list and statistics become self-validating records; the mergers (one
+        // per row of H while there are enough workgroups) poll for them: nothing to count.
+        if constexpr (WAVES >= 4) {
+            const Mailbox mb = a.mail;
+            for (int m = wave; m < a.M; m += WAVES) {
+                if (lane < a.k)
+                    publish(mb.rec + mail_rec_index(m, lane, gidx),
+                            mail_pack(run_val[m * a.k + lane], (unsigned)run_id[m * a.k + lane]));
+                if (lane == 0) publish(mb.st + mail_st_index(m, gidx), mail_pack_stats(run_ms[2 * m], run_ms[2 * m + 1]));
+            }
+            const int R = G < a.M ? G : a.M;
+            if (gidx >= R) return;
+            stamp(4);
+            merge_rows_mailbox(mb, part, a.ticket + 1, G, gidx, R, a.M, a.k, a.token_ids, a.logp, &s_merge,
+                               &s_select[0], nullptr);
+            __syncthreads();
+            stamp(5);
+        }
+        return;
+    }
     for (int m = wave; m < a.M; m += WAVES) {
         if (lane < a.k) {
             publish(part.val + part_index(m * a.k + lane, gidx), run_val[m * a.k + lane]);
@@ -323,7 +391,7 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
 }
 
 constexpr int kLdsBudget = 160 * 1024;
-constexpr int kStaticLdsReserve = 8 * 1024;   // room for the kernel's static LDS (selection scratch)
+constexpr int kStaticLdsReserve = 12 * 1024;   // room for the kernel's static LDS (selection scratch)
 
 struct Build {
     int mt16, hch;
@@ -389,15 +457,23 @@ fr_status launch_mfma(const HeadProblem &p, Sink sink, const fr_tuning *t, hipSt
     a.part.val = p.ws.part_val;
     a.part.id = p.ws.part_id;
     a.ticket = p.ws.ticket;
+    a.mail.rec = p.ws.mail_rec;
+    a.mail.st = p.ws.mail_st;
     a.token_ids = p.token_ids;
     a.logp = p.logp;
     a.z_out = p.z_out;
     a.z_ld = p.z_ld;
+    a.trace = t ? static_cast<long long *>(t->trace) : nullptr;
 
     int grid = cus < a.passes ? cus : a.passes;   // one persistent workgroup per compute unit
     if (t && t->grid > 0) grid = t->grid < a.passes ? t->grid : a.passes;
     if (grid > kGridMax) grid = kGridMax;
     if (grid_used) *grid_used = grid;
+
+    // Single launch through the result mailbox: its records cover 64 rows of H, 16 list
+    // positions and 256 workgroups, and the merge wants four wavefronts per workgroup.
+    a.mailbox = sink == Sink::kFusedTopk && p.k <= kMailK && p.M <= kMailRows && grid <= 4 * kWave &&
+                b->mt16 <= 4 && !(t && t->no_mailbox);
 
     fr_status st = FR_ERR_UNSUPPORTED;
     switch (b->mt16) {

@@ -128,6 +128,8 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     const Partials part = a.part;   // a local copy keeps the argument block itself in registers
 
     constexpr int ZR_MAX = FOLD_WAVES * kTileRows;   // local rows that the fold's lanes cover
+    // four rows of H per folding wavefront only where two would take a second round
+    constexpr bool kQuadFold = !SKEW && MT > 2 * FOLD_WAVES;
     constexpr int kStep16 = kLanesAlongD;        // 16-byte chunks per row per step
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -430,10 +432,10 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
             if (SKEW && wave >= FOLD_WAVES) {
                 // the ninth wavefront only streams
             } else if (p == first_pass) {
-                fold_pass<ZR_MAX, false, SKEW>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, 0, a.M, wave,
+                fold_pass<ZR_MAX, false, SKEW, kQuadFold>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, 0, a.M, wave,
                                                FOLD_WAVES, row_of, out, &s_select[wave]);
             } else {
-                fold_pass<ZR_MAX, true, SKEW>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, 0, a.M, wave,
+                fold_pass<ZR_MAX, true, SKEW, kQuadFold>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, 0, a.M, wave,
                                               FOLD_WAVES, row_of, out, &s_select[wave]);
             }
         }
@@ -632,7 +634,7 @@ fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hip
     a.mail.st = p.ws.mail_st;
     if (p.step) {
         // the expansion rides on the mailbox merge: k <= 16, one launch, at most 256 workgroups
-        if (sink != Sink::kFusedTopk || p.k > kSmallKMax || cus > 4 * kWave || p.M * p.k > kMailRows * kMailK)
+        if (sink != Sink::kFusedTopk || p.k > kSmallKMax || cus > 4 * kWave || p.M * p.k > kStepRows * kMailK)
             return FR_ERR_UNSUPPORTED;
         a.step = *p.step;
         a.step.rec = p.ws.step_rec;

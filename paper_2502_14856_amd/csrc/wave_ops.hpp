@@ -177,7 +177,7 @@ __device__ __forceinline__ unsigned long long make_key(unsigned hi, unsigned lo)
 
 // Per-wavefront LDS scratch of the threshold selection below.
 struct alignas(16) SelectScratch {
-    unsigned long long key[kWave];
+    unsigned long long key[2 * kWave];   // the four-row fold keeps 32 slots per row
     int pl[kWave];
 };
 
