@@ -300,7 +300,10 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
                 auto row_of = [&](int m) {
                     return FoldRow{z_all + m * (kZR + kZPad), run_ms + 2 * m, run_val + m * a.k, run_id + m * a.k};
                 };
-                const FoldSink out{FoldTo::kLds, Partials{}, Mailbox{}, 0, run_ms, run_val, run_id};
+                // the last pass of the workgroup writes its result out instead of keeping it
+                const bool last = p + G >= a.passes;
+                const FoldSink out{!last ? FoldTo::kLds : (a.mailbox ? FoldTo::kMailbox : FoldTo::kPartials),
+                                   a.part, a.mail, (int)blockIdx.x, run_ms, run_val, run_id};
                 constexpr bool kQuad = Mp > 2 * WAVES;   // two rows per wavefront would take several rounds
                 if (p == (int)blockIdx.x)
                     fold_pass<kZR, false, false, kQuad>(z_all, kZR + kZPad, 1, 0, ids_lds, n_valid, a.k, 0, a.M, wave,
@@ -335,8 +338,10 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
                     return FoldRow{z_stage + (m - mt * 16) * (kZR + kZPad), run_ms + 2 * m,
                                    run_val + m * a.k, run_id + m * a.k};
                 };
-                // the running state stays in LDS; it is written out once, after the last pass
-                const FoldSink out{FoldTo::kLds, Partials{}, Mailbox{}, 0, run_ms, run_val, run_id};
+                // the last pass of the workgroup writes its result out instead of keeping it
+                const bool last = p + G >= a.passes;
+                const FoldSink out{!last ? FoldTo::kLds : (a.mailbox ? FoldTo::kMailbox : FoldTo::kPartials),
+                                   a.part, a.mail, (int)blockIdx.x, run_ms, run_val, run_id};
                 constexpr bool kQuad = 16 > 2 * WAVES;
                 if (p == (int)blockIdx.x)
                     fold_pass<kZR, false, false, kQuad>(z_stage, kZR + kZPad, 1, 0, ids_lds, n_valid, a.k, mt * 16,
@@ -350,21 +355,15 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
 
     if (a.sink == (int)Sink::kLogits || a.sink == (int)Sink::kStreamOnly) return;
 
-    __syncthreads();
+    // (every workgroup's last fold has written its lists and statistics out)
     stamp(3);
     const int gidx = blockIdx.x;
     const Partials part = a.part;   // a local copy keeps the argument block itself in registers
     if (a.mailbox) {
-        // Every row's list and statistics become self-validating records; the mergers (one
-        // per row of H while there are enough workgroups) poll for them: nothing to count.
+        // The results are self-validating records; the mergers (one per row of H while there
+        // are enough workgroups) poll for them: nothing to count.
         if constexpr (WAVES >= 4) {
             const Mailbox mb = a.mail;
-            for (int m = wave; m < a.M; m += WAVES) {
-                if (lane < a.k)
-                    publish(mb.rec + mail_rec_index(m, lane, gidx),
-                            mail_pack(run_val[m * a.k + lane], (unsigned)run_id[m * a.k + lane]));
-                if (lane == 0) publish(mb.st + mail_st_index(m, gidx), mail_pack_stats(run_ms[2 * m], run_ms[2 * m + 1]));
-            }
             const int R = G < a.M ? G : a.M;
             if (gidx >= R) return;
             stamp(4);
@@ -374,13 +373,6 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
             stamp(5);
         }
         return;
-    }
-    for (int m = wave; m < a.M; m += WAVES) {
-        if (lane < a.k) {
-            publish(part.val + part_index(m * a.k + lane, gidx), run_val[m * a.k + lane]);
-            publish(part.id + part_index(m * a.k + lane, gidx), run_id[m * a.k + lane]);
-        }
-        if (lane < 2) publish(part.ms + part_index(m * 2 + lane, gidx), run_ms[2 * m + lane]);
     }
     if (a.sink == (int)Sink::kPartialsOnly) return;
 
