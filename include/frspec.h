@@ -113,7 +113,8 @@ fr_status fr_workspace_check(const void *workspace, size_t workspace_bytes, int3
  *   logp       out  fp32  [M, k]
  *   workspace       >= fr_workspace_bytes(M, d, V_sub, k) bytes, 16-byte aligned,
  *                   prepared by fr_workspace_init
- * Requires M >= 1, d % 8 == 0, 1 <= k <= min(V_sub, FR_K_MAX), V_sub < 2^31.
+ * Requires M >= 1, d % 8 == 0, 1 <= k <= min(V_sub, FR_K_MAX), V_sub < 2^31.  W_sub (rows
+ * rounded up to a multiple of 16) must not exceed 4 GiB, else FR_ERR_UNSUPPORTED.
  * M <= 16 runs in the skinny kernel (all of H resident in LDS, W streamed once through
  * registers); larger M, or an H too large for LDS, runs in the chunked matrix-core kernel
  * in slabs of up to 256 rows of H.

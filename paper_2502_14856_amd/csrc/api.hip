@@ -48,6 +48,8 @@ fr_status check_head_args(const void *H, int64_t M, int64_t d, const void *W, in
     if (M > INT32_MAX || d > (1 << 24)) return FR_ERR_INVALID_ARG;
     if (k < 1 || k > FR_K_MAX || k > V_rows) return FR_ERR_INVALID_ARG;
     if (V_rows * (d / 8) > INT32_MAX) return FR_ERR_INVALID_ARG;   // 16-byte chunk index fits int32
+    // the kernels address W as a base plus a 32-bit byte offset (tiles of 16 rows, padded)
+    if ((V_rows + 15) / 16 * 16 * d * 2 > (int64_t(1) << 32)) return FR_ERR_UNSUPPORTED;
     if (!aligned16(H) || !aligned16(W)) return FR_ERR_ALIGNMENT;
     return FR_OK;
 }

@@ -389,7 +389,7 @@ struct Build {
     int mt16, hch;
 };
 // m tiles -> H chunk length (in half-steps of 64 elements) of the build that serves them
-constexpr Build kBuilds[] = {{1, 4}, {2, 4}, {4, 4}, {8, 2}, {12, 1}, {16, 1}};
+constexpr Build kBuilds[] = {{1, 8}, {2, 8}, {4, 4}, {8, 2}, {12, 1}, {16, 1}};
 
 const Build *build_for(int M) {
     const int t = (M + 15) / 16;
@@ -469,8 +469,8 @@ fr_status launch_mfma(const HeadProblem &p, Sink sink, const fr_tuning *t, hipSt
 
     fr_status st = FR_ERR_UNSUPPORTED;
     switch (b->mt16) {
-        case 1: st = launch_one<1, 1, 8, 4, 4>(a, grid, lds, s); break;
-        case 2: st = launch_one<2, 1, 8, 4, 4>(a, grid, lds, s); break;
+        case 1: st = launch_one<1, 1, 8, 4, 8>(a, grid, lds, s); break;
+        case 2: st = launch_one<2, 1, 8, 4, 8>(a, grid, lds, s); break;
         case 4: st = launch_one<4, 1, 8, 4, 4>(a, grid, lds, s); break;
         case 8: st = launch_one<8, 2, 4, 2, 2>(a, grid, lds, s); break;
         case 12: st = launch_one<12, 2, 4, 2, 1>(a, grid, lds, s); break;

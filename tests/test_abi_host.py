@@ -13,7 +13,7 @@ from paper_2502_14856_amd.binding import Tuning
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "frspec.h")
 
-INVALID, ALIGN, WORKSPACE = -1, -2, -3
+INVALID, ALIGN, WORKSPACE, UNSUPPORTED = -1, -2, -3, -5
 
 
 def _declared_symbols():
@@ -67,6 +67,9 @@ def test_draft_topk_rejects_bad_arguments_before_any_launch():
     assert _draft(k=0) == INVALID
     assert _draft(k=65) == INVALID
     assert _draft(V=5, k=6) == INVALID
+    assert _draft(V=1 << 20, d=4096) == UNSUPPORTED       # 8 GiB of weights: beyond the 32-bit offsets
+    assert _draft(V=(1 << 19) + 1, d=4096) == UNSUPPORTED
+    assert _draft(V=1 << 19, d=4096, ws_bytes=1024) == WORKSPACE   # exactly 4 GiB passes the shape check
     assert _draft(H=0x1008) == ALIGN
     assert _draft(W=0x2004) == ALIGN
     assert _draft(ws=0x5008) == ALIGN

@@ -150,7 +150,7 @@ def test_tiny_config_draft_topk():
 @pytest.mark.parametrize("M,d,V,V_sub,k", [
     (1, 256, 4096, 1024, 1), (10, 512, 6000, 3000, 10), (16, 256, 5000, 2500, 16),
     (5, 264, 3000, 777, 7), (10, 1024, 9000, 4099, 33), (3, 128, 2000, 1999, 64),
-    (2, 64, 100, 10, 10), (10, 4096, 2000, 640, 10)])
+    (2, 64, 100, 10, 10), (10, 4096, 2000, 640, 10), (4, 8192, 3000, 1500, 8)])
 def test_draft_topk_skinny(M, d, V, V_sub, k):
     _say("draft skinny", M, d, V, V_sub, k)
     W, H, r = _case(V, d, M, 5)
@@ -165,7 +165,7 @@ def test_draft_topk_skinny(M, d, V, V_sub, k):
 @pytest.mark.parametrize("M,d,V,V_sub,k", [
     (17, 256, 4096, 1024, 4), (60, 512, 6000, 3000, 10), (64, 256, 5000, 2500, 16),
     (100, 264, 3000, 777, 7), (256, 128, 3000, 1500, 10), (300, 64, 2000, 900, 5),
-    (40, 128, 2000, 1999, 64)])
+    (40, 128, 2000, 1999, 64), (10, 8192, 3000, 1500, 10), (33, 8192, 1200, 700, 16)])
 def test_draft_topk_matrix_core(M, d, V, V_sub, k):
     _say("draft mfma", M, d, V, V_sub, k)
     W, H, r = _case(V, d, M, 6)
