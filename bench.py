@@ -186,6 +186,28 @@ def main() -> int:
             off += Mstep * k
         return fr.fr_tree_select(*hist, off, K)
     t_phase_fused = timed(draft_phase_fused, 100, 5)
+    # the same phase captured once in a HIP graph (step s reads copy s of W_sub) and replayed
+    sel_out = [torch.empty(K, dtype=torch.int32, device="cuda") for _ in range(4)] + \
+              [torch.empty((K, K), dtype=torch.uint8, device="cuda")]
+    nodes = [(node_score[:1], node_hist[:1])] + \
+            [(torch.empty(width, dtype=torch.float32, device="cuda"), torch.empty(width, dtype=torch.int32, device="cuda"))
+             for _ in range(depth)]
+
+    def draft_phase_static():
+        off = 0
+        for step in range(depth):
+            Mstep = 1 if step == 0 else width
+            fr.fr_draft_step(H[:Mstep], copies[step % N_COPIES], idx_map, k, nodes[step][0], nodes[step][1],
+                             min(width, Mstep * k), *hist, off, ws, token_ids=ids[:Mstep], logp=logp[:Mstep],
+                             next_score=nodes[step + 1][0], next_token=nxt[1], next_hist=nodes[step + 1][1])
+            off += Mstep * k
+        fr.fr_tree_select(*hist, off, K, out=sel_out)
+    draft_phase_static()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        draft_phase_static()
+    t_phase_graph = timed(lambda i: graph.replay(), 100, 5)
     t_step_fused = timed(lambda i: fr.fr_draft_step(H, copies[i % N_COPIES], idx_map, k, node_score, node_hist, width,
                                                     *hist, k, ws, token_ids=ids, logp=logp, next_score=nxt[0],
                                                     next_token=nxt[1], next_hist=nxt[2]),
@@ -270,8 +292,12 @@ def main() -> int:
             "draft_phase_depth6_us": t_phase * 1e6,
             "draft_step_fused_us": t_step_fused * 1e6,
             "draft_phase_fused_depth6_us": t_phase_fused * 1e6,
+            "draft_phase_fused_graph_replay_us": t_phase_graph * 1e6,
             "draft_phase_note": "6 x (fr_draft_topk + fr_beam_expand) + fr_tree_select (K=60), width 10; fused = "
                                 "6 x fr_draft_step (expansion inside the LM head's launch) + fr_tree_select; "
+                                "graph_replay = the fused phase captured once in a HIP graph; beam_expand_us and "
+                                "tree_select_us are call-to-call times of back-to-back launches from Python (launch-"
+                                "bound; the kernels themselves take about 4 and 11 us, see profiles/); "
                                 "the draft model's transformer layer is not part of this build",
             "count_tokens_gtok_per_s": n_tok / t_count / 1e9,
             "count_tokens_us_per_2p26": t_count * 1e6,

@@ -395,17 +395,28 @@ def fr_draft_step(H, W_sub, idx_map, k: int, node_score, node_hist, width: int, 
     return token_ids, logp, next_score, next_token, next_hist
 
 
-def fr_tree_select(hist_score, hist_token, hist_parent, N: int, K: int, stream=None):
+def fr_tree_select(hist_score, hist_token, hist_parent, N: int, K: int, stream=None, out=None):
     """The draft tree (Section 2): the K best of the first N history entries.  Returns
-    (sel_index, sel_token, sel_parent, sel_depth, tree_mask[K, K] uint8)."""
+    (sel_index, sel_token, sel_parent, sel_depth, tree_mask[K, K] uint8); `out`, if given, is
+    that tuple preallocated (int32 [K] four times, uint8 [K, K])."""
     _dev(hist_score, torch.float32, "hist_score")
     _dev(hist_token, torch.int32, "hist_token")
     _dev(hist_parent, torch.int32, "hist_parent")
     if min(hist_score.numel(), hist_token.numel(), hist_parent.numel()) < N:
         raise ValueError("history arrays are shorter than N")
     dev = hist_score.device
-    out = [torch.empty(K, dtype=torch.int32, device=dev) for _ in range(4)]
-    mask = torch.empty((K, K), dtype=torch.uint8, device=dev)
+    if out is not None:
+        *out, mask = out
+        for t in out:
+            _dev(t, torch.int32, "out")
+            if t.numel() < K:
+                raise ValueError("selection outputs are shorter than K")
+        _dev(mask, torch.uint8, "tree_mask")
+        if mask.numel() < K * K:
+            raise ValueError("tree_mask is smaller than K * K")
+    else:
+        out = [torch.empty(K, dtype=torch.int32, device=dev) for _ in range(4)]
+        mask = torch.empty((K, K), dtype=torch.uint8, device=dev)
     _check(lib().fr_tree_select(_ptr(hist_score), _ptr(hist_token), _ptr(hist_parent), N, K, _ptr(out[0]),
                                 _ptr(out[1]), _ptr(out[2]), _ptr(out[3]), _ptr(mask), _stream(stream)),
            "fr_tree_select")
