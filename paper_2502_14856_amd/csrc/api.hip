@@ -110,7 +110,8 @@ fr_status head_topk(const void *H, int64_t M, int64_t d, const void *W, const in
         return launch_skinny(p, stream_only ? Sink::kStreamOnly : two_launch ? Sink::kPartialsOnly : Sink::kFusedTopk, tuning, s);
     }
 
-    // matrix-core path: slabs of H rows, each a full pass over W
+    // matrix-core path: slabs of H rows, each a full pass over W (a build costs the same for
+    // any number of rows up to its size, so full slabs first beat equal shares)
     const int slab = mfma_max_rows(k);
     if (slab <= 0) return FR_ERR_UNSUPPORTED;
     for (int64_t m0 = 0; m0 < M; m0 += slab) {

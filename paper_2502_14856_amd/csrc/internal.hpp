@@ -78,10 +78,10 @@ fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hip
 // Largest LDS the skinny kernel would need, for workspace-free feasibility checks.
 bool skinny_fits(int M, int d, int k);
 
-// mfma.hip: matrix-core kernel for 1 <= M <= 256.
+// mfma.hip: matrix-core kernel for 1 <= M <= 128 (more rows run in slabs).
 fr_status launch_mfma(const HeadProblem &p, Sink sink, const fr_tuning *t, hipStream_t s,
                       int *grid_used);
-// Largest slab of H rows (multiple of 16, <= 256) whose per-row state fits LDS for this k.
+// Largest slab of H rows (multiple of 16, <= 128) whose per-row state fits LDS for this k.
 int mfma_max_rows(int k);
 
 // merge.hip: merges G partial slots per row of H into the outputs.

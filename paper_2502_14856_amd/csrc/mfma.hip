@@ -55,13 +55,12 @@ struct WideArgs {
 __host__ __device__ constexpr int wide_round_up(int x, int m) { return (x + m - 1) / m * m; }
 
 struct WideLds {
-    int h_off, stage_off, z_off, ids_off, ms_off, val_off, id_off, total;
+    int h_off, stage_off, ids_off, ms_off, val_off, id_off, total;
     __host__ __device__ WideLds(int MT16, int HCH, int k) {
         const int Mp = MT16 * 16;
         int o = 0;
         h_off = o;     o += 2 * Mp * (HCH * 8 + 1) * 16;
         stage_off = o; o += kZR * kStagePitch16 * 16;
-        z_off = o;     o += 16 * (kZR + kZPad) * 4;
         ids_off = o;   o += kZR * 4;
         ms_off = o;    o += Mp * 2 * 4;
         val_off = o;   o += Mp * k * 4;
@@ -85,7 +84,6 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
     const WideLds L(MT16, HCH, a.k);
     u32x4 *H_lds = reinterpret_cast<u32x4 *>(base + L.h_off);
     u32x4 *stage_lds = reinterpret_cast<u32x4 *>(base + L.stage_off);
-    float *z_stage = reinterpret_cast<float *>(base + L.z_off);
     int *ids_lds = reinterpret_cast<int *>(base + L.ids_off);
     float *run_ms = reinterpret_cast<float *>(base + L.ms_off);
     float *run_val = reinterpret_cast<float *>(base + L.val_off);
@@ -182,7 +180,7 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
     for (; p < a.passes; p += G) {
         const int pass_row0 = p * kZR;
         const int n_valid = min(kZR, a.V_rows - pass_row0);
-        __syncthreads();   // the previous pass is done with ids_lds, z_stage and the H buffers
+        __syncthreads();   // the previous pass is done with ids_lds and the H buffers (its logits)
         if (tid < n_valid) {
             const int row = pass_row0 + tid;
             ids_lds[tid] = a.idx_map ? a.idx_map[row] : row;
@@ -274,12 +272,12 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
         }
 
         // ---- consume the pass ----
-        // While the logits of all Mp rows fit into the two H buffers (no longer needed once
-        // the products are done), they go there in one piece and every wavefront folds its
-        // rows of H without meeting the others again.
-        constexpr bool kAllAtOnce = 2 * HP * 16 >= (kZR + kZPad) * 4;
+        // The logits of all Mp rows go into the two H buffers (no longer needed once the
+        // products are done) in one piece, and every wavefront folds its rows of H without
+        // meeting the others again.
+        static_assert(2 * HP * 16 >= (kZR + kZPad) * 4, "the H buffers hold the logits of a pass");
         stamp(2);
-        if constexpr (kAllAtOnce) {
+        {
             float *z_all = reinterpret_cast<float *>(H_lds);
             __syncthreads();   // every wavefront is done with the H chunks
 #pragma clang loop unroll(full)
@@ -311,44 +309,6 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
                 else
                     fold_pass<kZR, true, false, kQuad>(z_all, kZR + kZPad, 1, 0, ids_lds, n_valid, a.k, 0, a.M, wave,
                                                        WAVES, row_of, out, &s_select[wave]);
-            }
-            continue;
-        }
-        // Otherwise one tile of 16 H rows at a time (fully unrolled whatever its size: a rolled
-        // loop would index the accumulators dynamically and push them to scratch memory).
-#pragma clang loop unroll(full)
-        for (int mt = 0; mt < MT16; ++mt) {
-            __syncthreads();   // z_stage is free (and, the first time, the last H chunk is done with)
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb) {
-                float *dst = z_stage + j * (kZR + kZPad) + (wave * RB + rb) * 16 + 4 * g;
-                *reinterpret_cast<f32x4_t *>(dst) = acc[rb][mt];
-            }
-            __syncthreads();
-            if (a.sink == (int)Sink::kLogits) {
-                for (int e = tid; e < 16 * kZR; e += NT) {
-                    const int ml = e / kZR, r = e - ml * kZR;
-                    const int m = mt * 16 + ml;
-                    if (m < a.M && r < n_valid)
-                        a.z_out[(size_t)m * a.z_ld + pass_row0 + r] = z_stage[ml * (kZR + kZPad) + r];
-                }
-            } else if (a.sink != (int)Sink::kStreamOnly) {
-                const int m_end = min(a.M, mt * 16 + 16);
-                auto row_of = [&](int m) {
-                    return FoldRow{z_stage + (m - mt * 16) * (kZR + kZPad), run_ms + 2 * m,
-                                   run_val + m * a.k, run_id + m * a.k};
-                };
-                // the last pass of the workgroup writes its result out instead of keeping it
-                const bool last = p + G >= a.passes;
-                const FoldSink out{!last ? FoldTo::kLds : (a.mailbox ? FoldTo::kMailbox : FoldTo::kPartials),
-                                   a.part, a.mail, (int)blockIdx.x, run_ms, run_val, run_id};
-                constexpr bool kQuad = 16 > 2 * WAVES;
-                if (p == (int)blockIdx.x)
-                    fold_pass<kZR, false, false, kQuad>(z_stage, kZR + kZPad, 1, 0, ids_lds, n_valid, a.k, mt * 16,
-                                                        m_end, wave, WAVES, row_of, out, &s_select[wave]);
-                else
-                    fold_pass<kZR, true, false, kQuad>(z_stage, kZR + kZPad, 1, 0, ids_lds, n_valid, a.k, mt * 16,
-                                                       m_end, wave, WAVES, row_of, out, &s_select[wave]);
             }
         }
     }
@@ -389,7 +349,7 @@ struct Build {
     int mt16, hch;
 };
 // m tiles -> H chunk length (in half-steps of 64 elements) of the build that serves them
-constexpr Build kBuilds[] = {{1, 8}, {2, 8}, {4, 4}, {8, 2}, {12, 1}, {16, 1}};
+constexpr Build kBuilds[] = {{1, 8}, {2, 8}, {4, 4}, {8, 2}};
 
 const Build *build_for(int M) {
     const int t = (M + 15) / 16;
@@ -417,7 +377,7 @@ fr_status launch_one(const WideArgs &a, int grid, int lds, hipStream_t s) {
 
 }  // namespace
 
-// Largest slab of H rows (multiple of 16, <= 256) whose per-row state fits LDS for this k.
+// Largest slab of H rows (multiple of 16, <= 128) whose per-row state fits LDS for this k.
 int mfma_max_rows(int k) {
     int best = 0;
     for (const Build &b : kBuilds)
@@ -472,9 +432,7 @@ fr_status launch_mfma(const HeadProblem &p, Sink sink, const fr_tuning *t, hipSt
         case 1: st = launch_one<1, 1, 8, 4, 8>(a, grid, lds, s); break;
         case 2: st = launch_one<2, 1, 8, 4, 8>(a, grid, lds, s); break;
         case 4: st = launch_one<4, 1, 8, 4, 4>(a, grid, lds, s); break;
-        case 8: st = launch_one<8, 2, 4, 2, 2>(a, grid, lds, s); break;
-        case 12: st = launch_one<12, 2, 4, 2, 1>(a, grid, lds, s); break;
-        case 16: st = launch_one<16, 2, 4, 2, 1>(a, grid, lds, s); break;
+        case 8: st = launch_one<8, 1, 8, 4, 2>(a, grid, lds, s); break;
     }
     if (st != FR_OK) return st;
     if (sink == Sink::kPartialsOnly) return launch_merge(p, grid, s);
