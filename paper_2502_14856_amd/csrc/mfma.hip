@@ -321,14 +321,17 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
     const Partials part = a.part;   // a local copy keeps the argument block itself in registers
     if (a.mailbox) {
         // The results are self-validating records; the mergers (one per row of H while there
-        // are enough workgroups) poll for them: nothing to count.
+        // are enough workgroups) poll for them: nothing to count.  The mergers are the LAST
+        // workgroups of the grid: workgroups start in order, so everything a merger waits for
+        // is already on the machine (or done) and waits for nothing itself, however few
+        // compute units the launch was given.
         if constexpr (WAVES >= 4) {
             const Mailbox mb = a.mail;
             const int R = G < a.M ? G : a.M;
-            if (gidx >= R) return;
+            if (gidx < G - R) return;
             stamp(4);
-            merge_rows_mailbox(mb, part, a.ticket + 1, G, gidx, R, a.M, a.k, a.token_ids, a.logp, &s_merge,
-                               &s_select[0], nullptr);
+            merge_rows_mailbox(mb, part, a.ticket + 1, G, gidx - (G - R), R, a.M, a.k, a.token_ids, a.logp,
+                               &s_merge, &s_select[0], nullptr);
             __syncthreads();
             stamp(5);
         }
