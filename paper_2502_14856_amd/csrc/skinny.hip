@@ -451,16 +451,20 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     if (mailbox) {
         // Mailbox records announce themselves: nothing to wait for, nothing to count.  The
         // mergers are fixed, every 8th workgroup while there are enough (workgroups are
-        // dealt to the 8 dies in turn, so these share the first die), and start polling
-        // for the others' records as soon as their own are out.
+        // dealt to the 8 dies in turn, so these share the first die), counted from the END of
+        // the grid: workgroups start in order, so everything a merger waits for is already
+        // on the machine (or done) and waits for nothing itself.  They start polling for the
+        // others' records as soon as their own are out.
         const int spread = 8 * (R - 1) < G ? 8 : 1;
         const int b = (int)blockIdx.x;
-        if (b % spread != 0 || b / spread >= R) return;
+        const int top = (G - 1) / spread * spread;   // the last workgroup that can be a merger
+        const int r = (top - b) / spread;
+        if (b > top || b % spread != 0 || r >= R) return;
         stamp(4);
-        merge_rows_mailbox(a.mail, part, a.ticket + 1, G, b / spread, R, a.M, a.k, a.token_ids, a.logp, &s_merge,
+        merge_rows_mailbox(a.mail, part, a.ticket + 1, G, r, R, a.M, a.k, a.token_ids, a.logp, &s_merge,
                            &s_select[0], a.step.rec);
         // the first merger also runs the beam-search expansion of the step, if one was asked for
-        if (a.step.rec && b == 0 && wave == 0)
+        if (a.step.rec && r == 0 && wave == 0)
             expand_step_fused(a.step, a.M, a.k, reinterpret_cast<unsigned long long *>(s_select), a.ticket + 1);
     } else {
         const int r = arrive_and_wait(ar, (unsigned)__builtin_amdgcn_readfirstlane((int)turn), G, R, &s_slot);
