@@ -322,9 +322,9 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
     if (a.mailbox) {
         // The results are self-validating records; the mergers (one per row of H while there
         // are enough workgroups) poll for them: nothing to count.  The mergers are the LAST
-        // workgroups of the grid: workgroups start in order, so everything a merger waits for
-        // is already on the machine (or done) and waits for nothing itself, however few
-        // compute units the launch was given.
+        // workgroups of the grid: workgroups start in order, so once the R <= 64 mergers are on
+        // the machine everything else they wait for is running or done, and waits for nothing
+        // itself: the wait ends as long as R workgroups fit on the device at once.
         if constexpr (WAVES >= 4) {
             const Mailbox mb = a.mail;
             const int R = G < a.M ? G : a.M;

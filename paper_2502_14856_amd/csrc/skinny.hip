@@ -452,9 +452,9 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
         // Mailbox records announce themselves: nothing to wait for, nothing to count.  The
         // mergers are fixed, every 8th workgroup while there are enough (workgroups are
         // dealt to the 8 dies in turn, so these share the first die), counted from the END of
-        // the grid: workgroups start in order, so everything a merger waits for is already
-        // on the machine (or done) and waits for nothing itself.  They start polling for the
-        // others' records as soon as their own are out.
+        // the grid: workgroups start in order, so once the R <= 16 mergers are on the machine
+        // everything else they wait for is running or done, and waits for nothing itself.
+        // They start polling for the others' records as soon as their own are out.
         const int spread = 8 * (R - 1) < G ? 8 : 1;
         const int b = (int)blockIdx.x;
         const int top = (G - 1) / spread * spread;   // the last workgroup that can be a merger
