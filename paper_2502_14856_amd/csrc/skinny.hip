@@ -106,11 +106,32 @@ struct SkinnyLds {
  * wavefront's pace is set by the latency of its die's memory path, not by its own byte
  * count, so it does not matter which wavefront of a die carries fewer or more rows.)
  */
-template <int MT, int WAVES, int DEPTH, bool MFMA, bool TILED = false, bool SKEW = false>
+template <int MT, int WAVES, int DEPTH, bool MFMA, bool TILED = false, bool SKEW = false, int HR = 16>
 __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     static_assert(MFMA || !TILED, "the tiled layout is the matrix cores' operand order");
     static_assert(!SKEW || (MFMA && !TILED), "the skewed build is the default build plus one wavefront");
     constexpr int FOLD_WAVES = SKEW ? WAVES - 1 : WAVES;
+    // The argument block spans several cache lines and the compiler fetches its fields where
+    // they are first used, in half a dozen dependent rounds of scalar loads, each a trip to
+    // memory (the block is new with every launch).  One load per line, all issued at once,
+    // brings the lines into the scalar cache in a single trip; the rounds then hit.
+    {
+        static_assert(sizeof(SkinnyArgs) <= 6 * 64, "one load per 64-byte line of the argument block");
+        typedef const __attribute__((address_space(4))) unsigned *ConstWords;
+        ConstWords ka = (ConstWords)__builtin_amdgcn_kernarg_segment_ptr();
+        unsigned w0, w1, w2, w3, w4, w5;
+        asm volatile(
+            "s_load_dword %0, %6, 0x0\n\t"
+            "s_load_dword %1, %6, 0x40\n\t"
+            "s_load_dword %2, %6, 0x80\n\t"
+            "s_load_dword %3, %6, 0xc0\n\t"
+            "s_load_dword %4, %6, 0x100\n\t"
+            "s_load_dword %5, %6, 0x140\n\t"
+            "s_waitcnt lgkmcnt(0)"
+            : "=&s"(w0), "=&s"(w1), "=&s"(w2), "=&s"(w3), "=&s"(w4), "=&s"(w5)
+            : "s"(ka)
+            : "memory");
+    }
     extern __shared__ u32x4 smem[];
     char *base = reinterpret_cast<char *>(smem);
     const int hrows = MFMA ? a.M : MT;
@@ -213,33 +234,53 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     // Requested the other way round, H would queue behind 16 W loads per lane.
     // Thread t fetches 16-byte column t of every row of H (wave-uniform base + 32-bit lane
     // offset, like W), holds the pieces in registers and writes them to LDS further down.
+    // Every load between here and the first products is issued UNCONDITIONALLY (rows past M
+    // re-read row 0, rows past the pass are clamped): a load under a branch leaves the
+    // compiler without the number of loads outstanding behind it, and it then waits for
+    // all of them (vmcnt(0)), i.e. for the whole first batch of W, before H goes to LDS.
     constexpr int NT = WAVES * kWave;
-    constexpr int kHRowsMax = SKEW ? 12 : 16;   // (the skewed build's LDS holds at most 11 rows of H)
+    // rows of H this build requests (the skewed build's LDS holds at most 11, the vector-ALU
+    // builds are compiled per number of rows anyway)
+    constexpr int kHRowsMax = SKEW ? 12 : (MFMA ? HR : MT);
     const GlobalBytes Hb = (GlobalBytes)a.H;
     const unsigned hcol = (unsigned)min(tid, a.d8 - 1) * 16u;   // clamped: always a valid address
+    // token id of local row `tid` of a pass (asked for before the loads of that pass's W)
+    const int *idx_or_null = a.idx_map;
+    auto request_id = [&](int pass) {
+        const int row = min((SKEW ? blk_row0 : pass * ZR) + (tid < ZR_MAX + 16 ? tid : 0), a.V_rows - 1);
+        return idx_or_null ? __builtin_nontemporal_load(idx_or_null + row) : row;
+    };
+    int id_next = request_id((int)blockIdx.x < a.passes ? (int)blockIdx.x : 0);
     u32x4 hpre[kHRowsMax];
 #pragma unroll
     for (int m = 0; m < kHRowsMax; ++m)
-        if (m < hrows)   // wave-uniform; rows past M (zero padding) re-read row 0
-            hpre[m] = *reinterpret_cast<GlobalVec>(Hb + (m < a.M ? a.row_delta[m] : 0ll) + hcol);
+        hpre[m] = *reinterpret_cast<GlobalVec>(Hb + (m < a.M ? a.row_delta[m] : 0ll) + hcol);
     u32x4 wb[DEPTH][kRowsPerLane];
     unsigned wo[kRowsPerLane];
     const int first_pass = (int)blockIdx.x;
-    int p = first_pass;
-    if (p < a.passes && groups > 0) {
+    int p = first_pass;   // (the host launches no more workgroups than there are passes)
+    // The first DEPTH stages of W, also unconditionally: when the row has fewer steps than
+    // the pipeline is deep the surplus loads are clamped into the matrix and never used.
+    {
+        const unsigned w_last = ((unsigned)(TILED ? a.tiles * kTileRows : a.V_rows) * (unsigned)a.d8 - 1u) * 16u;
         row_offsets(p, wo);
 #pragma unroll
         for (int u = 0; u < DEPTH; ++u)
 #pragma unroll
             for (int r = 0; r < kRowsPerLane; ++r)
-                wb[u][r] = load_w(Wb, wo[r] + g_first * kGroupBytes + u * kStepBytes);
+                wb[u][r] = load_w(Wb, min(wo[r] + g_first * kGroupBytes + u * kStepBytes, w_last));
     }
-
-    // stage H (zero padded to whole steps, and to MT rows where the tiles need it)
+    // stage H (zero padded to whole steps, and to MT rows where the tiles need it).  Every
+    // piece of H is waited for here, in issue order and in straight-line code, whether it is
+    // written or not: the count of loads behind it (those of W) is then exact, and no
+    // register of an unwritten row is still awaited when it is reused.
 #pragma unroll
-    for (int m = 0; m < kHRowsMax; ++m)
+    for (int m = 0; m < kHRowsMax; ++m) {
+        asm volatile("" : "+v"(hpre[m]));
         if (m < hrows && tid < hcols)
             H_lds[m * hpitch + tid] = (tid < a.d8 && m < a.M) ? hpre[m] : zero_u32x4();
+    }
+    asm volatile("" : "+v"(id_next));   // (requested before H: here by now, and known to be)
     for (int c = tid + NT; c < hcols; c += NT) {   // columns past the first NT: not held in registers
 #pragma unroll
         for (int m = 0; m < 16; ++m)
@@ -256,10 +297,7 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     for (; p < a.passes && (!SKEW || p == first_pass); p += G) {
         const int pass_row0 = SKEW ? blk_row0 : p * ZR;
         const int n_valid = SKEW ? blk_rows : min(ZR, a.V_rows - pass_row0);
-        if (tid < n_valid) {
-            const int row = pass_row0 + tid;
-            ids_lds[tid] = a.idx_map ? a.idx_map[row] : row;
-        }
+        if (tid < n_valid) ids_lds[tid] = id_next;
 
         // Accumulators.  Vector-ALU variant: the lane's share (16 bytes per step) of 4 rows x
         // MT rows of H.  Matrix-core variant: one 16 x 16 tile, lane (j, g) = column m = j,
@@ -353,6 +391,7 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
             const int cg = c_begin + grp * (DEPTH * kStep16);
             const bool has_next = !SKEW && p + G < a.passes;   // (the skewed build has one pass)
             if (has_next) {
+                id_next = request_id(p + G);
                 row_offsets(p + G, wo);
                 const unsigned nofs = (unsigned)g_first * kGroupBytes;
 #pragma unroll
@@ -364,6 +403,7 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
                         wb[u][r] = load_w(Wb, wo[r] + nofs + u * kStepBytes);
                     __builtin_amdgcn_sched_barrier(0);
                 }
+                asm volatile("" : "+v"(id_next));   // wait for it here, where the loads behind it are counted
             } else {
 #pragma unroll
                 for (int u = 0; u < DEPTH; ++u) compute(wb[u], cg + u * kStep16);
@@ -439,7 +479,14 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
                                               FOLD_WAVES, row_of, out, &s_select[wave]);
             }
         }
-        if (p + G < a.passes) __syncthreads();
+        if (p + G < a.passes) {
+            // (with a pipelined stream the ids of the next pass were requested together with its W)
+            if (groups == 0 && !SKEW) {
+                id_next = request_id(p + G);
+                asm volatile("" : "+v"(id_next));
+            }
+            __syncthreads();
+        }
     }
 
     if (a.sink == (int)Sink::kLogits || a.sink == (int)Sink::kStreamOnly) return;
@@ -489,9 +536,9 @@ int bucket_for(int M) {
     return -1;
 }
 
-template <int MT, int WAVES, int DEPTH, bool MFMA, bool TILED = false, bool SKEW = false>
+template <int MT, int WAVES, int DEPTH, bool MFMA, bool TILED = false, bool SKEW = false, int HR = 16>
 fr_status launch_one(const SkinnyArgs &a, int grid, int lds, hipStream_t s) {
-    auto kern = skinny_kernel<MT, WAVES, DEPTH, MFMA, TILED, SKEW>;
+    auto kern = skinny_kernel<MT, WAVES, DEPTH, MFMA, TILED, SKEW, HR>;
     static bool attr_done = false;   // raising the dynamic LDS limit is idempotent
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -677,7 +724,15 @@ fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hip
 
     fr_status st;
     switch (variant) {
-        case 0: st = launch_one<kMfmaTile, 8, 4, true>(a, grid, lds, s); break;
+        case 0:
+            // the default build exists once per number of H rows it requests at its start
+            if (a.M <= 2) st = launch_one<kMfmaTile, 8, 4, true, false, false, 2>(a, grid, lds, s);
+            else if (a.M <= 4) st = launch_one<kMfmaTile, 8, 4, true, false, false, 4>(a, grid, lds, s);
+            else if (a.M <= 8) st = launch_one<kMfmaTile, 8, 4, true, false, false, 8>(a, grid, lds, s);
+            else if (a.M <= 10) st = launch_one<kMfmaTile, 8, 4, true, false, false, 10>(a, grid, lds, s);
+            else if (a.M <= 12) st = launch_one<kMfmaTile, 8, 4, true, false, false, 12>(a, grid, lds, s);
+            else st = launch_one<kMfmaTile, 8, 4, true>(a, grid, lds, s);
+            break;
         case 1: st = launch_one<kMfmaTile, 4, 8, true>(a, grid, lds, s); break;
         case 2: st = launch_one<kMfmaTile, 8, 3, true>(a, grid, lds, s); break;
         case 3: st = launch_one<kMfmaTile, 8, 6, true>(a, grid, lds, s); break;
