@@ -129,16 +129,21 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
     };
 
     // H chunk c = elements [c * HCH * 64, (c + 1) * HCH * 64) of d, all Mp rows (zero padded)
+    // Every load is issued unconditionally, from a clamped (always valid) address: a load
+    // under a branch leaves the compiler without the number of loads outstanding behind
+    // it, and it then waits for all of them (vmcnt(0)), which would drain the W pipeline at
+    // every chunk.  What must read as zero is masked when the chunk is written to LDS.
     u32x4 hreg[kHLoads];
+    unsigned hvalid = 0u;   // bit u: piece u of the fetched chunk is inside H
     auto h_fetch = [&](int c) {
+        hvalid = 0u;
 #pragma unroll
         for (int u = 0; u < kHLoads; ++u) {
             const int e = tid + u * NT;
             const int row = e / (HCH * 8), c16 = e - row * (HCH * 8);
             const int col = c * (HCH * 8) + c16;
-            u32x4 v = zero_u32x4();
-            if (e < Mp * HCH * 8 && row < a.M && col < a.d8) v = a.H[(size_t)row * a.d8 + col];
-            hreg[u] = v;
+            hreg[u] = a.H[(size_t)min(row, a.M - 1) * a.d8 + min(col, a.d8 - 1)];
+            if (e < Mp * HCH * 8 && row < a.M && col < a.d8) hvalid |= 1u << u;
         }
     };
     auto h_store = [&](int buf) {
@@ -146,7 +151,7 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
         for (int u = 0; u < kHLoads; ++u) {
             const int e = tid + u * NT;
             const int row = e / (HCH * 8), c16 = e - row * (HCH * 8);
-            if (e < Mp * HCH * 8) H_lds[(buf * Mp + row) * HP + c16] = hreg[u];
+            if (e < Mp * HCH * 8) H_lds[(buf * Mp + row) * HP + c16] = ((hvalid >> u) & 1u) ? hreg[u] : zero_u32x4();
         }
     };
 
@@ -169,24 +174,40 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
             for (int r = 0; r < kRowsPerLane; ++r)
                 wb[u][rb][r] = load_w(Wb, wo[rb][r] + (unsigned)s * kStepBytes);
     };
+    // token id of local row `tid` of a pass: asked for before that pass's loads of W, so that
+    // waiting for it does not mean waiting for them
+    const int *idx_or_null = a.idx_map;
+    auto request_id = [&](int pass) {
+        const int row = min(pass * kZR + (tid < kZR ? tid : 0), a.V_rows - 1);
+        return idx_or_null ? __builtin_nontemporal_load(idx_or_null + row) : row;
+    };
 
+    // Start of the stream (the host launches no more workgroups than there are passes): the
+    // ids and the first H chunk are requested first, the first DEPTH steps of W right behind
+    // them, all unconditionally (when the row has fewer steps than the pipeline is deep the
+    // surplus loads are clamped into the matrix and never used).
     int p = blockIdx.x;
-    if (p < a.passes && groups > 0) {
+    const int first_chunk = (2 * step_at(0)) / HCH;
+    int id_next = request_id(p);
+    h_fetch(first_chunk);
+    {
+        const unsigned w_last = ((unsigned)a.V_rows * (unsigned)a.d8 - 1u) * 16u;
         row_offsets(p, wo);
 #pragma unroll
-        for (int u = 0; u < DEPTH; ++u) w_issue(u, step_at(u));
+        for (int u = 0; u < DEPTH; ++u)
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int r = 0; r < kRowsPerLane; ++r)
+                    wb[u][rb][r] = load_w(Wb, min(wo[rb][r] + (unsigned)step_at(u) * kStepBytes, w_last));
     }
 
     for (; p < a.passes; p += G) {
         const int pass_row0 = p * kZR;
         const int n_valid = min(kZR, a.V_rows - pass_row0);
         __syncthreads();   // the previous pass is done with ids_lds and the H buffers (its logits)
-        if (tid < n_valid) {
-            const int row = pass_row0 + tid;
-            ids_lds[tid] = a.idx_map ? a.idx_map[row] : row;
-        }
-        h_fetch((2 * step_at(0)) / HCH);
-        h_store(0);
+        if (tid < n_valid) ids_lds[tid] = id_next;
+        h_store(0);   // the first chunk: fetched at the start, or while the previous pass drained
 
         f32x4_t acc[RB][MT16];
 #pragma unroll
@@ -196,19 +217,22 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
 
         // Step number i of the visiting order; its 16 x 128 slab(s) of W are in `w`.  The two
         // halves of a step may lie in different H chunks.
+        // `sub0` = (2 * i) % HCH: a compile-time constant in the unrolled pipelined steps.
         bool have_next = false;
-        auto process_step = [&](int i, const u32x4 (&w)[RB][kRowsPerLane]) {
+        auto process_step = [&](int i, int sub0, const u32x4 (&w)[RB][kRowsPerLane]) {
             bf16x8_t af[RB][4];
 #pragma unroll
             for (int hs = 0; hs < 2; ++hs) {
                 const int h = 2 * i + hs;          // half-step number in visiting order
-                const int sub = h % HCH;           // its place inside the current H chunk
+                const int sub = (sub0 + hs) % HCH; // its place inside the current H chunk
                 const int buf = (h / HCH) & 1;
                 if (sub == 0) {
                     __syncthreads();               // the chunk in `buf` is complete; the other buffer is free
                     const int h2 = h + HCH;
                     have_next = h2 < 2 * a.steps;
-                    if (have_next) h_fetch((2 * step_at(h2 >> 1) + (h2 & 1)) / HCH);
+                    // always a fetch: behind the last chunk of a pass comes the first one again,
+                    // which the next pass (if there is one) starts with
+                    h_fetch(have_next ? (2 * step_at(h2 >> 1) + (h2 & 1)) / HCH : first_chunk);
                 }
                 if (hs == 0) {
                     // transpose the slab into operand order through this wavefront's staging rows
@@ -236,24 +260,48 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
                                                                                   acc[rb][mt], 0, 0, 0);
                     }
                 }
-                if (sub == HCH - 1 && have_next) h_store(buf ^ 1);
+                if (sub == HCH - 1) {
+                    // (pinned behind the products: the wait for the chunk belongs here, not before them)
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (have_next) h_store(buf ^ 1);
+                }
             }
         };
 
+        // Steady state: consume stage u, refill it with the same stage of the next group
+        // (unconditionally: the drain below is a copy of its own).
         int i = 0;
-        for (int grp = 0; grp < groups; ++grp) {
-            const bool last = grp == groups - 1;
-            const bool has_next_pass = p + G < a.passes;
-            if (last && has_next_pass) row_offsets(p + G, wo);
+        for (int grp = 0; grp + 1 < groups; ++grp) {
 #pragma unroll
             for (int u = 0; u < DEPTH; ++u) {
-                process_step(i, wb[u]);
+                process_step(i, (2 * u) % HCH, wb[u]);
                 __builtin_amdgcn_sched_barrier(0);
-                if (!last) w_issue(u, step_at(i + DEPTH));
-                else if (has_next_pass) w_issue(u, step_at(u));
+                w_issue(u, step_at(i + DEPTH));
                 __builtin_amdgcn_sched_barrier(0);
                 ++i;
             }
+        }
+        if (groups > 0) {
+            if (p + G < a.passes) {   // the stages freed here start on the next pass of this workgroup
+                id_next = request_id(p + G);
+                row_offsets(p + G, wo);
+#pragma unroll
+                for (int u = 0; u < DEPTH; ++u) {
+                    process_step(i, (2 * u) % HCH, wb[u]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    w_issue(u, step_at(u));
+                    __builtin_amdgcn_sched_barrier(0);
+                    ++i;
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < DEPTH; ++u) {
+                    process_step(i, (2 * u) % HCH, wb[u]);
+                    ++i;
+                }
+            }
+        } else if (p + G < a.passes) {
+            id_next = request_id(p + G);
         }
         if (i < a.steps) {
             // Leftover steps, not pipelined.  A chunk index past the end of the row is clamped:
@@ -267,7 +315,7 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
                 for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
                     for (int r = 0; r < kRowsPerLane; ++r) w[rb][r] = load_w(Wb, wr[rb][r] + (unsigned)c * 16u);
-                process_step(i, w);
+                process_step(i, (2 * i) % HCH, w);
             }
         }
 
