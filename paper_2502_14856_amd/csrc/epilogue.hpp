@@ -1042,7 +1042,11 @@ __device__ __forceinline__ void merge_rows_mailbox(const Mailbox &mb, const Part
             const float bound = value_of_key_hi(row16_kth_largest_u32(gm, k));
 
             // ---- survivors among this wavefront's entries: not below the bound (a NaN
-            // is not below anything, and ranks first like in the key order)
+            // is not below anything, and ranks first like in the key order).  First all
+            // the survivor masks, then ONE reservation of LDS slots for the wavefront, then
+            // the few registers that hold a survivor are written out.
+            unsigned long long mk[TPW][HPL];
+            unsigned total = 0u;
 #pragma unroll
             for (int j = 0; j < TPW; ++j)
 #pragma unroll
@@ -1050,17 +1054,27 @@ __device__ __forceinline__ void merge_rows_mailbox(const Mailbox &mb, const Part
                     const int id = (int)(unsigned)ent[j][q];
                     const float v = mail_hi(ent[j][q]);
                     const bool real = (wave + j * NW < k) && (lane + kWave * q < G) && id != INT_MAX && id != -1;
-                    const bool sv = real && !(v < bound);
-                    const unsigned long long mk = __ballot(sv);
-                    if (mk != 0ull) {
-                        unsigned base = 0u;
-                        if (lane == 0) base = atomicAdd(&ms->count, (unsigned)__popcll(mk));
-                        const int pos = __builtin_amdgcn_readfirstlane((int)base) +
-                                        (int)__builtin_amdgcn_mbcnt_hi((unsigned)(mk >> 32),
-                                                                       __builtin_amdgcn_mbcnt_lo((unsigned)mk, 0u));
-                        if (sv && pos < kWave) ms->key[pos] = make_key(key_hi_of(v), ~(unsigned)id);
-                    }
+                    mk[j][q] = __ballot(real && !(v < bound));
+                    total += (unsigned)__popcll(mk[j][q]);
                 }
+            if (total != 0u) {
+                unsigned base = 0u;
+                if (lane == 0) base = atomicAdd(&ms->count, total);
+                int at = __builtin_amdgcn_readfirstlane((int)base);
+#pragma unroll
+                for (int j = 0; j < TPW; ++j)
+#pragma unroll
+                    for (int q = 0; q < HPL; ++q) {
+                        const unsigned long long m1 = mk[j][q];
+                        if (m1 != 0ull) {
+                            const int pos = at + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(m1 >> 32),
+                                                                                __builtin_amdgcn_mbcnt_lo((unsigned)m1, 0u));
+                            if (((m1 >> lane) & 1ull) && pos < kWave)
+                                ms->key[pos] = make_key(key_hi_of(mail_hi(ent[j][q])), ~(unsigned)ent[j][q]);
+                            at += (int)__popcll(m1);
+                        }
+                    }
+            }
             if (wave == NW - 1) {
                 // log Z = mx + log sum_g S_g exp(mx_g - mx)
                 float mxs[HPL], Ss[HPL];
