@@ -405,12 +405,12 @@ __device__ __forceinline__ bool fold_pair_fast(const float *z_lds, int z_row_str
     }
     const float v_x = ok_x ? z_x : kNegInf;
     if (WITH_EXTRA) lmax = fmaxf(lmax, v_x);
-    const float mx = fmaxf(old_mx, row16_max_f32(fmaxf(lmax, swap16_f32(lmax))));
+    const float mx = fmaxf(old_mx, row16_max_f32(max_xor16_f32(lmax)));
     float part = 0.0f;
 #pragma unroll
     for (int c = 0; c < C; ++c) part += exp_diff(v[c], mx);
     if (WITH_EXTRA) part += exp_diff(v_x, mx);
-    part += swap16_f32(part);
+    part = sum_xor16_f32(part);
     const float S = old_S * exp_diff(old_mx, mx) + row16_sum_all(part);
 
     // candidates as keys, and the bound
@@ -431,7 +431,7 @@ __device__ __forceinline__ bool fold_pair_fast(const float *z_lds, int z_row_str
     unsigned lm = hi[0];
 #pragma unroll
     for (int c = 1; c < CPL; ++c) lm = max(lm, hi[c]);
-    const unsigned L = row16_kth_largest_u32(max(lm, swap16_u32(lm)), k);
+    const unsigned L = row16_kth_largest_u32(max_xor16_u32(lm), k);
 
     // survivors of each half, packed into its 32 scratch slots
     sc->key[lane] = 0ull;
@@ -1037,8 +1037,8 @@ __device__ __forceinline__ void merge_rows_mailbox(const Mailbox &mb, const Part
 #pragma unroll
             for (int q = 0; q < HPL; ++q) lmax = fmaxf(lmax, lane + kWave * q < G ? mail_hi(head[q]) : kNegInf);
             unsigned gm = key_hi_of(lmax);
-            gm = max(gm, swap16_u32(gm));
-            gm = max(gm, swap32_u32(gm));
+            gm = max_xor16_u32(gm);
+            gm = max_xor32_u32(gm);
             const float bound = value_of_key_hi(row16_kth_largest_u32(gm, k));
 
             // ---- survivors among this wavefront's entries: not below the bound (a NaN

@@ -121,17 +121,27 @@ __device__ __forceinline__ float row16_sum_all(float v) {
     v += dpp_f32<kDppRowMirror>(v);
     return v;
 }
-// Exchange with the lane 16 away inside each group of 32 lanes (crossbar only, no LDS
-// memory), and with the lane 32 away.
-constexpr int kSwizzleSwap16 = 0x401F;   // bit mode: and 0x1f, or 0, xor 0x10
-__device__ __forceinline__ unsigned swap16_u32(unsigned v) {
-    return (unsigned)__builtin_amdgcn_ds_swizzle((int)v, kSwizzleSwap16);
+// v[l] combined with v[l ^ 16] (v[l ^ 32]) in every lane, through the lane-swap instructions
+// of the vector ALU (v_permlane16_swap / v_permlane32_swap): given the same value in both
+// operands, one result holds v[l] and the other v[l ^ 16] in every lane, in one order or
+// the other, which is all a commutative combination needs.  No trip through the LDS pipe.
+__device__ __forceinline__ unsigned max_xor16_u32(unsigned v) {
+    const auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    return max((unsigned)r[0], (unsigned)r[1]);
 }
-__device__ __forceinline__ float swap16_f32(float v) {
-    return __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), kSwizzleSwap16));
+__device__ __forceinline__ unsigned max_xor32_u32(unsigned v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return max((unsigned)r[0], (unsigned)r[1]);
 }
-__device__ __forceinline__ unsigned swap32_u32(unsigned v) {
-    return (unsigned)__builtin_amdgcn_ds_bpermute((lane_id() ^ 32) << 2, (int)v);
+__device__ __forceinline__ float max_xor16_f32(float v) {
+    const auto r = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, v), __builtin_bit_cast(unsigned, v),
+                                                    false, false);
+    return fmaxf(__builtin_bit_cast(float, (unsigned)r[0]), __builtin_bit_cast(float, (unsigned)r[1]));
+}
+__device__ __forceinline__ float sum_xor16_f32(float v) {
+    const auto r = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, v), __builtin_bit_cast(unsigned, v),
+                                                    false, false);
+    return __builtin_bit_cast(float, (unsigned)r[0]) + __builtin_bit_cast(float, (unsigned)r[1]);
 }
 // The k-th largest (1 <= k <= 16, counted with multiplicity) of the 16 values held by the
 // lanes of a DPP row, returned to every lane of the row: the smallest value that has
