@@ -1096,24 +1096,22 @@ __device__ __forceinline__ void merge_rows_mailbox(const Mailbox &mb, const Part
         }
         __syncthreads();
 
-        // Every wavefront has its records: they are emptied for the next call, each record by
-        // the wavefront that owns its list position, the statistics by the last one.  The first
-        // wavefront does that after the row's outputs are on their way.
-        auto empty_my_records = [&]() {
+        // Every fetching wavefront has its records in registers: they are emptied for the next
+        // call by all wavefronts but the first, which ranks and writes the outputs meanwhile
+        // (emptying needs the addresses only, so the wavefronts that fetched nothing help).
+        {
+            const int helpers = (int)blockDim.x / kWave - 1;
+            if (wave > 0) {
+                for (int t = wave - 1; t < k; t += helpers)
 #pragma unroll
-            for (int q = 0; q < HPL; ++q) {
-                const int g = lane + kWave * q;
-                if (g < G) {
+                    for (int q = 0; q < HPL; ++q)
+                        if (lane + kWave * q < G) publish(mb.rec + mail_rec_index(m, t, lane + kWave * q), kMailEmpty);
+                if (wave == helpers)
 #pragma unroll
-                    for (int j = 0; j < TPW; ++j) {
-                        const int t = wave + j * NW;
-                        if (t < k) publish(mb.rec + mail_rec_index(m, t, g), kMailEmpty);
-                    }
-                    if (wave == NW - 1) publish(mb.st + mail_st_index(m, g), kMailEmpty);
-                }
+                    for (int q = 0; q < HPL; ++q)
+                        if (lane + kWave * q < G) publish(mb.st + mail_st_index(m, lane + kWave * q), kMailEmpty);
             }
-        };
-        if (wave > 0 && wave < NW) empty_my_records();
+        }
 
         const int n = __builtin_amdgcn_readfirstlane((int)ms->count);
         if (n <= kWave) {
@@ -1140,12 +1138,10 @@ __device__ __forceinline__ void merge_rows_mailbox(const Mailbox &mb, const Part
                     logp[(size_t)m * k + lane] = kNegInf;
                     if (step_rec) publish(step_rec + m * kMailK + lane, mail_pack(kNegInf, (unsigned)INT_MAX));
                 }
-                empty_my_records();
             }
         } else {
             // Too many survivors (heavily tied values): hand the row to the general merge
             // through the plain partial arrays.
-            if (wave == 0) empty_my_records();
             if (wave < NW) {
 #pragma unroll
                 for (int q = 0; q < HPL; ++q) {
