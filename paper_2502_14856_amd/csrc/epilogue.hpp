@@ -968,12 +968,13 @@ __device__ __forceinline__ void expand_step_fused(const StepArgs &st, int M, int
  * skipped), the survivors meet in LDS, and the first wavefront ranks them and writes
  * the outputs.  The records are emptied for the next call on the way.
  */
+template <int NW = 4>   // fetching wavefronts: 4 or 8, at most the wavefronts of the workgroup
 __device__ __forceinline__ void merge_rows_mailbox(const Mailbox &mb, const Partials &P, unsigned *error, int G,
                                                    int first, int stride, int M, int k, int *token_ids,
                                                    float *logp, MergeScratch *ms, SelectScratch *sc,
                                                    unsigned long long *step_rec) {
     constexpr int HPL = 4;                      // G <= 256
-    constexpr int NW = 4;                       // fetching wavefronts
+    static_assert(NW == 4 || NW == 8, "list positions are dealt out evenly");
     constexpr int TPW = kMailK / NW;            // list positions per fetching wavefront
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x / kWave);

@@ -378,7 +378,7 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
             const int R = G < a.M ? G : a.M;
             if (gidx < G - R) return;
             stamp(4);
-            merge_rows_mailbox(mb, part, a.ticket + 1, G, gidx - (G - R), R, a.M, a.k, a.token_ids, a.logp,
+            merge_rows_mailbox<(WAVES >= 8 ? 8 : 4)>(mb, part, a.ticket + 1, G, gidx - (G - R), R, a.M, a.k, a.token_ids, a.logp,
                                &s_merge, &s_select[0], nullptr);
             __syncthreads();
             stamp(5);

@@ -508,7 +508,7 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
         const int r = (top - b) / spread;
         if (b > top || b % spread != 0 || r >= R) return;
         stamp(4);
-        merge_rows_mailbox(a.mail, part, a.ticket + 1, G, r, R, a.M, a.k, a.token_ids, a.logp, &s_merge,
+        merge_rows_mailbox<(WAVES >= 8 ? 8 : 4)>(a.mail, part, a.ticket + 1, G, r, R, a.M, a.k, a.token_ids, a.logp, &s_merge,
                            &s_select[0], a.step.rec);
         // the first merger also runs the beam-search expansion of the step, if one was asked for
         if (a.step.rec && r == 0 && wave == 0)
