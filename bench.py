@@ -277,7 +277,7 @@ def main() -> int:
                    "d": d, "V": V, "V_sub": V_sub, "M": M, "k": k},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                      "frac": achieved / PEAK_HBM_GBPS, "traffic": traffic,
-                     "kernel": "skinny_kernel<16,8,4,true> (matrix-core build, one launch per call: stream, fold, mailbox merge)",
+                     "kernel": "skinny_kernel<16,8,4,true,false,false,10> (matrix-core build, one launch per call: stream, fold, mailbox merge)",
                      "algorithmic_bytes_per_launch": bytes_per_call},
         "cpu_baseline": cpu,
         "extra": {
