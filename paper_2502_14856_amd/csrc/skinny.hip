@@ -132,6 +132,19 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
             : "s"(ka)
             : "memory");
     }
+    // The very first thing: H (see "Start of the stream" below for the order of the loads).
+    // Thread t fetches 16-byte column t of every row of H (wave-uniform base + 32-bit lane
+    // offset, like W), holds the pieces in registers and writes them to LDS further down.
+    // rows of H this build requests (the skewed build's LDS holds at most 11, the vector-ALU
+    // builds are compiled per number of rows anyway)
+    constexpr int kHRowsMax = SKEW ? 12 : (MFMA ? HR : MT);
+    const GlobalBytes Hb = (GlobalBytes)a.H;
+    const unsigned hcol = (unsigned)min((int)threadIdx.x, a.d8 - 1) * 16u;   // clamped: always a valid address
+    u32x4 hpre[kHRowsMax];
+#pragma unroll
+    for (int m = 0; m < kHRowsMax; ++m)
+        hpre[m] = *reinterpret_cast<GlobalVec>(Hb + (m < a.M ? a.row_delta[m] : 0ll) + hcol);
+
     extern __shared__ u32x4 smem[];
     char *base = reinterpret_cast<char *>(smem);
     const int hrows = MFMA ? a.M : MT;
@@ -239,11 +252,6 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     // compiler without the number of loads outstanding behind it, and it then waits for
     // all of them (vmcnt(0)), i.e. for the whole first batch of W, before H goes to LDS.
     constexpr int NT = WAVES * kWave;
-    // rows of H this build requests (the skewed build's LDS holds at most 11, the vector-ALU
-    // builds are compiled per number of rows anyway)
-    constexpr int kHRowsMax = SKEW ? 12 : (MFMA ? HR : MT);
-    const GlobalBytes Hb = (GlobalBytes)a.H;
-    const unsigned hcol = (unsigned)min(tid, a.d8 - 1) * 16u;   // clamped: always a valid address
     // token id of local row `tid` of a pass (asked for before the loads of that pass's W)
     const int *idx_or_null = a.idx_map;
     auto request_id = [&](int pass) {
@@ -251,10 +259,6 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
         return idx_or_null ? __builtin_nontemporal_load(idx_or_null + row) : row;
     };
     int id_next = request_id((int)blockIdx.x < a.passes ? (int)blockIdx.x : 0);
-    u32x4 hpre[kHRowsMax];
-#pragma unroll
-    for (int m = 0; m < kHRowsMax; ++m)
-        hpre[m] = *reinterpret_cast<GlobalVec>(Hb + (m < a.M ? a.row_delta[m] : 0ll) + hcol);
     u32x4 wb[DEPTH][kRowsPerLane];
     unsigned wo[kRowsPerLane];
     const int first_pass = (int)blockIdx.x;
