@@ -1,4 +1,5 @@
-// Wide kernel for many H rows (16 < M <= 256): Eq. 4 as a dense contraction
+// Wide kernel for many H rows (up to 128 per launch; more rows run as several launches):
+// Eq. 4 as a dense contraction
 // [V_rows x d] x [d x M] on v_mfma_f32_16x16x32_bf16, fused with the same online
 // log-softmax / top-k / remap epilogue as the skinny kernel.
 //
@@ -12,8 +13,9 @@
 //     every wavefront reads its B fragments from there;
 //   * accumulators hold z[16 rows x 16 m] per (row block, m tile): lane (j, g) owns rows
 //     4g..4g+3 of column m = j.
-// Three builds: 8 wavefronts x 16 rows for M <= 64 (bound by HBM), 4 wavefronts x 32 rows
-// for M <= 128 and M <= 256 (matrix cores and LDS close to the HBM stream).
+// Four builds, all 8 wavefronts x 16 rows: 1, 2, 4 or 8 tiles of 16 rows of H (M <= 16, 32, 64,
+// 128), with H chunks of 512, 512, 256 and 128 elements; bound by HBM up to about 100 rows of
+// H, by the matrix cores and the LDS reads of the H fragments beyond.
 #include "epilogue.hpp"
 #include "internal.hpp"
 
@@ -121,7 +123,11 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
     const int full_steps = a.d8 / kStep16;
     const int groups = full_steps / DEPTH;
     const int np = groups * DEPTH;
-    const int g_first = groups > 0 ? (int)(blockIdx.x % (unsigned)groups) : 0;
+    // (workgroup b runs on compute die b % 8: with an even number of groups, b % groups alone
+    // would give all workgroups of a die the same columns at any moment, and the dies then
+    // finish up to 7 us apart; the second term spreads every die over all the groups)
+    const int g_first =
+        groups > 0 ? (int)((blockIdx.x + ((groups & 1) ? 0u : blockIdx.x >> 3)) % (unsigned)groups) : 0;
     auto step_at = [&](int i) {
         if (i >= np) return i;
         int s = g_first * DEPTH + i;
