@@ -116,8 +116,9 @@ fr_status fr_workspace_check(const void *workspace, size_t workspace_bytes, int3
  * Requires M >= 1, d % 8 == 0, 1 <= k <= min(V_sub, FR_K_MAX), V_sub < 2^31.  W_sub (rows
  * rounded up to a multiple of 16) must not exceed 4 GiB, else FR_ERR_UNSUPPORTED.
  * M <= 16 runs in the skinny kernel (all of H resident in LDS, W streamed once through
- * registers); larger M, or an H too large for LDS, runs in the chunked matrix-core kernel
- * in slabs of up to 128 rows of H (one pass over W_sub per slab).
+ * registers) while H fits beside the kernel's other LDS buffers (12 rows at d = 4096);
+ * larger M, or a larger H, runs in the chunked matrix-core kernel in slabs of up to 128
+ * rows of H (one pass over W_sub per slab).
  * NaN or infinite inputs give unspecified outputs but never a fault or a hang.
  */
 fr_status fr_draft_topk(const void *H, int64_t M, int64_t d,

@@ -96,7 +96,14 @@ fr_status head_topk(const void *H, int64_t M, int64_t d, const void *W, const in
         if (path == 1 || path == 2 || M > kSkinnyMaxM || (d % 128) != 0) return FR_ERR_UNSUPPORTED;
         path = 3;
     }
-    if (path == 0) path = (M <= kSkinnyMaxM && skinny_fits((int)M, (int)d, k)) ? 3 : 2;
+    if (path == 0) {
+        // the skinny kernel while its eight-wavefront build holds H; beyond that the chunked
+        // kernel is faster than the four-wavefront build, which remains for the calls that
+        // only the skinny kernel serves (H rows in several blocks, the fused beam-search step)
+        const bool skinny_only = row_delta || step;
+        path = (M <= kSkinnyMaxM && (skinny_only ? skinny_fits((int)M, (int)d, k)
+                                                 : skinny_fits_eight_waves((int)M, (int)d, k))) ? 3 : 2;
+    }
     if ((row_delta || step) && path == 2) return FR_ERR_UNSUPPORTED;
     const bool two_launch = tuning && tuning->two_launch;
     const bool stream_only = tuning && tuning->stream_only;

@@ -73,10 +73,13 @@ constexpr int kSkinnyMaxM = 16;          // rows of H the vector-ALU kernel cove
 // Number of compute units of the current device (cached per device); <= 0 on error.
 int device_cu_count();
 
-// skinny.hip: vector-ALU kernel for M <= 16.  Returns FR_ERR_UNSUPPORTED if H does not fit LDS.
+// skinny.hip: kernel for M <= 16 with all of H in LDS.  Returns FR_ERR_UNSUPPORTED if H does not fit.
 fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hipStream_t s);
-// Largest LDS the skinny kernel would need, for workspace-free feasibility checks.
+// Whether some build of the skinny kernel can hold this problem's H in LDS ...
 bool skinny_fits(int M, int d, int k);
+// ... and whether its default build (eight wavefronts) can: the four-wavefront build that
+// takes over otherwise streams more slowly than the chunked kernel.
+bool skinny_fits_eight_waves(int M, int d, int k);
 
 // mfma.hip: matrix-core kernel for 1 <= M <= 128 (more rows run in slabs).
 fr_status launch_mfma(const HeadProblem &p, Sink sink, const fr_tuning *t, hipStream_t s,

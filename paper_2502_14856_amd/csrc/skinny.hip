@@ -629,6 +629,8 @@ bool skinny_fits(int M, int d, int k) {
     return M <= kSkinnyMaxM && default_variant(M, d, k, false, false) >= 0;
 }
 
+bool skinny_fits_eight_waves(int M, int d, int k) { return M <= kSkinnyMaxM && variant_fits(M, d, k, 0); }
+
 fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hipStream_t s) {
     if (p.M > kSkinnyMaxM) return FR_ERR_UNSUPPORTED;
     const bool vector_alu = t && t->path == 1;
