@@ -127,9 +127,9 @@ fr_status head_topk(const void *H, int64_t M, int64_t d, const void *W, const in
         p.M = rows;
         p.token_ids = token_ids + m0 * k;
         p.logp = logp + m0 * k;
-        // Single launch while the result mailbox covers the rows (k <= 16, up to 64 rows), or,
+        // Single launch while the result mailbox covers the rows (k <= 16, up to 128 rows), or,
         // through the arrival counter, while the rows are few; else a merge launch follows.
-        const bool mail_ok = k <= 16 && rows <= 64 && !(tuning && tuning->no_mailbox);
+        const bool mail_ok = k <= kMailK && rows <= kMailRows && !(tuning && tuning->no_mailbox);
         const Sink sink = stream_only ? Sink::kStreamOnly
                           : (two_launch || (rows > 32 && !mail_ok)) ? Sink::kPartialsOnly : Sink::kFusedTopk;
         st = launch_mfma(p, sink, tuning, s, nullptr);

@@ -65,7 +65,6 @@ struct Mailbox {
     unsigned long long *rec;
     unsigned long long *st;
 };
-constexpr int kMailRows = 64, kMailK = 16;   // rows of H and list positions with records
 constexpr int kStepRows = 16;                 // rows of H whose results the fused expansion collects
 constexpr unsigned long long kMailEmpty = ~0ull;
 constexpr unsigned kMailSpinLimit = 1u << 20;   // rounds of about a microsecond before giving up

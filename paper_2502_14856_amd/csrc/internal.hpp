@@ -61,10 +61,11 @@ struct HeadProblem {
 };
 
 constexpr size_t kWorkspaceHeaderBytes = 512;
-// Result mailbox of the single-launch merge: 64 rows of H x (16 list positions + 1
+// Result mailbox of the single-launch merge: 128 rows of H x (16 list positions + 1
 // statistics record) x 512 workgroups, 8 bytes each, all ones while empty.
-constexpr size_t kMailRecBytes = 64u * 16u * 512u * 8u;
-constexpr size_t kMailStBytes = 64u * 512u * 8u;
+constexpr int kMailRows = 128, kMailK = 16;   // rows of H and list positions with records
+constexpr size_t kMailRecBytes = (size_t)kMailRows * kMailK * 512u * 8u;
+constexpr size_t kMailStBytes = (size_t)kMailRows * 512u * 8u;
 constexpr size_t kStepRecBytes = 16u * 16u * 8u;   // one record per (row of H, list position)
 constexpr int kWorkspaceGridMax = 512;   // partial slots reserved per row of H
 constexpr int kMatrixPathMaxM = 256;     // rows of H per matrix-core launch

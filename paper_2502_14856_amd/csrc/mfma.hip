@@ -13,8 +13,8 @@
 //     every wavefront reads its B fragments from there;
 //   * accumulators hold z[16 rows x 16 m] per (row block, m tile): lane (j, g) owns rows
 //     4g..4g+3 of column m = j.
-// Four builds, all 8 wavefronts x 16 rows: 1, 2, 4 or 8 tiles of 16 rows of H (M <= 16, 32, 64,
-// 128), with H chunks of 512, 512, 256 and 128 elements; bound by HBM up to about 100 rows of
+// Six builds, all 8 wavefronts x 16 rows: 1, 2, 3, 4, 6 or 8 tiles of 16 rows of H (M <= 16, 32,
+// 48, 64, 96, 128), with H chunks of 512, 512, 512, 256, 256 and 128 elements; bound by HBM up to about 100 rows of
 // H, by the matrix cores and the LDS reads of the H fragments beyond.
 #include "epilogue.hpp"
 #include "internal.hpp"
@@ -45,7 +45,7 @@ struct WideArgs {
     int sink;
     Partials part;
     Mailbox mail;
-    int mailbox;  // the results go through the mailbox records (single launch, k <= 16, M <= 64)
+    int mailbox;  // the results go through the mailbox records (single launch, k <= 16, M <= 128)
     unsigned *ticket;
     int *token_ids;
     float *logp;
@@ -376,7 +376,7 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
     if (a.mailbox) {
         // The results are self-validating records; the mergers (one per row of H while there
         // are enough workgroups) poll for them: nothing to count.  The mergers are the LAST
-        // workgroups of the grid: workgroups start in order, so once the R <= 64 mergers are on
+        // workgroups of the grid: workgroups start in order, so once the R <= 128 mergers are on
         // the machine everything else they wait for is running or done, and waits for nothing
         // itself: the wait ends as long as R workgroups fit on the device at once.
         if constexpr (WAVES >= 4) {
@@ -406,12 +406,13 @@ struct Build {
     int mt16, hch;
 };
 // m tiles -> H chunk length (in half-steps of 64 elements) of the build that serves them
-constexpr Build kBuilds[] = {{1, 8}, {2, 8}, {4, 4}, {8, 2}};
+constexpr Build kBuilds[] = {{1, 8}, {2, 8}, {3, 8}, {4, 4}, {6, 4}, {8, 2}};
 
-const Build *build_for(int M) {
+// the smallest build that covers M rows and whose LDS (it grows with k) fits
+const Build *build_for(int M, int k) {
     const int t = (M + 15) / 16;
     for (const Build &b : kBuilds)
-        if (t <= b.mt16) return &b;
+        if (t <= b.mt16 && WideLds(b.mt16, b.hch, k).total <= kLdsBudget - kStaticLdsReserve) return &b;
     return nullptr;
 }
 
@@ -444,7 +445,7 @@ int mfma_max_rows(int k) {
 
 fr_status launch_mfma(const HeadProblem &p, Sink sink, const fr_tuning *t, hipStream_t s,
                       int *grid_used) {
-    const Build *b = build_for(p.M);
+    const Build *b = build_for(p.M, p.k);
     if (!b) return FR_ERR_UNSUPPORTED;
     const int lds = WideLds(b->mt16, b->hch, p.k).total;
     if (lds > kLdsBudget - kStaticLdsReserve) return FR_ERR_UNSUPPORTED;
@@ -479,16 +480,18 @@ fr_status launch_mfma(const HeadProblem &p, Sink sink, const fr_tuning *t, hipSt
     if (grid > kGridMax) grid = kGridMax;
     if (grid_used) *grid_used = grid;
 
-    // Single launch through the result mailbox: its records cover 64 rows of H, 16 list
+    // Single launch through the result mailbox: its records cover 128 rows of H, 16 list
     // positions and 256 workgroups, and the merge wants four wavefronts per workgroup.
     a.mailbox = sink == Sink::kFusedTopk && p.k <= kMailK && p.M <= kMailRows && grid <= 4 * kWave &&
-                b->mt16 <= 4 && !(t && t->no_mailbox);
+                !(t && t->no_mailbox);
 
     fr_status st = FR_ERR_UNSUPPORTED;
     switch (b->mt16) {
         case 1: st = launch_one<1, 1, 8, 4, 8>(a, grid, lds, s); break;
         case 2: st = launch_one<2, 1, 8, 4, 8>(a, grid, lds, s); break;
+        case 3: st = launch_one<3, 1, 8, 4, 8>(a, grid, lds, s); break;
         case 4: st = launch_one<4, 1, 8, 4, 4>(a, grid, lds, s); break;
+        case 6: st = launch_one<6, 1, 8, 4, 4>(a, grid, lds, s); break;
         case 8: st = launch_one<8, 1, 8, 4, 2>(a, grid, lds, s); break;
     }
     if (st != FR_OK) return st;

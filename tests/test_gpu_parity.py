@@ -95,7 +95,7 @@ def test_logits_skinny_within_tolerance(M, d, V):
 
 
 @pytest.mark.parametrize("M,d,V", [(17, 256, 2048), (60, 512, 1000), (64, 4096, 300), (100, 264, 333),
-                                   (256, 256, 513), (300, 128, 260)])
+                                   (256, 256, 513), (300, 128, 260), (45, 1024, 500), (90, 520, 333)])
 def test_logits_matrix_core_within_tolerance(M, d, V):
     _say("logits mfma", M, d, V)
     W, H, _ = _case(V, d, M, 4)
@@ -165,7 +165,8 @@ def test_draft_topk_skinny(M, d, V, V_sub, k):
 @pytest.mark.parametrize("M,d,V,V_sub,k", [
     (17, 256, 4096, 1024, 4), (60, 512, 6000, 3000, 10), (64, 256, 5000, 2500, 16),
     (100, 264, 3000, 777, 7), (256, 128, 3000, 1500, 10), (300, 64, 2000, 900, 5),
-    (40, 128, 2000, 1999, 64), (10, 8192, 3000, 1500, 10), (33, 8192, 1200, 700, 16)])
+    (40, 128, 2000, 1999, 64), (10, 8192, 3000, 1500, 10), (33, 8192, 1200, 700, 16),
+    (80, 256, 3000, 1500, 10), (96, 512, 2000, 1000, 12), (44, 4096, 1500, 1100, 10)])
 def test_draft_topk_matrix_core(M, d, V, V_sub, k):
     _say("draft mfma", M, d, V, V_sub, k)
     W, H, r = _case(V, d, M, 6)
@@ -272,19 +273,20 @@ def test_workspace_reuse_with_changing_inputs_sees_no_stale_partials():
 
 
 def test_one_workspace_across_changing_shapes_leaves_the_mailbox_empty():
-    # The single-launch merge (skinny kernel, and the chunked kernel up to 64 rows of H)
+    # The single-launch merge (skinny kernel, and the chunked kernel up to 128 rows of H)
     # passes results through self-validating records that must all be empty again when a
     # call ends, whatever M, k, the kernel and the number of workgroups were; a record left
     # behind would be taken for a result by a later call.
     _say("workspace reuse, changing shapes")
     W, _, r = _case(9000, 256, 16, 21)
-    ws = fr.new_workspace(64, 256, 9000, 16)
+    ws = fr.new_workspace(128, 256, 9000, 16)
     W_d, r_d = to_dev_bf16(W), to_dev_i32(r)
     g = np.random.default_rng(22)
     shapes = [(10, 10, 4096, {}), (3, 16, 9000, {}), (16, 1, 100, {}), (10, 10, 4096, dict(grid=5)),
               (1, 7, 2048, dict(ksplit=2)), (12, 12, 6000, {}), (10, 10, 4096, dict(path=1)), (16, 16, 9000, {}),
               (40, 10, 4096, {}), (10, 10, 4096, dict(path=2)), (64, 16, 9000, {}), (17, 3, 300, {}),
-              (40, 10, 4096, dict(no_mailbox=1)), (33, 1, 9000, dict(grid=7)), (10, 10, 4096, {})]
+              (40, 10, 4096, dict(no_mailbox=1)), (33, 1, 9000, dict(grid=7)), (100, 10, 9000, {}),
+              (128, 16, 4096, {}), (90, 5, 9000, dict(grid=9)), (10, 10, 4096, {})]
     for rep in range(2):
         for M, k, V_sub, knobs in shapes:
             H = f32_to_bf16_bits(g.standard_normal((M, 256)).astype(np.float32))
@@ -299,7 +301,7 @@ def test_one_workspace_across_changing_shapes_leaves_the_mailbox_empty():
             ids_g, lp_g = fr.fr_draft_topk(to_dev_bf16(H), W_g, idx_g, k, ws, tuning=t)
             _sync()
             check_topk_against_oracle(ids_g.cpu().numpy(), lp_g.cpu().numpy(), z_o, idx_o, ids_o, lp_o)
-            mail = ws[512:512 + (64 * 16 + 64) * 512 * 8].cpu().numpy()
+            mail = ws[512:512 + (128 * 16 + 128) * 512 * 8].cpu().numpy()
             assert (mail == 0xFF).all(), (M, k, V_sub, knobs)
             head = ws[:512].cpu().numpy().view(np.uint32)
             assert head[1] == 0      # no wait ever timed out
