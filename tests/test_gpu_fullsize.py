@@ -135,6 +135,29 @@ def test_batched256_shape_sampled_rows():
     _sampled_rows_check("batched256", rows=12, full=False)
 
 
+def test_every_build_of_the_chunked_kernel_at_full_size():
+    # the batched configuration's weights and ranking with the first M of its 256 rows of H: one
+    # M per build of the chunked kernel (16, 32, 48, 64, 96 and 128 rows; the 8-wavefront skinny
+    # kernel stops at 12 rows for d = 4096)
+    c = CONFIGS["batched256"]
+    _say("generating", c.name)
+    W = make_weights(c.V, c.d, c.index)
+    H = make_hidden(c.M, c.d, c.index)
+    r, _ = zipf_ranking(c.V, c.zipf_s, c.n_tokens, c.index)
+    W_g, idx_g = fr.fr_build_subset(to_dev_bf16(W), to_dev_i32(r), c.V_sub)
+    W_o, idx_o = oracle.build_subset(W, r, c.V_sub)
+    assert np.array_equal(idx_g.cpu().numpy(), idx_o)
+    ws = fr.new_workspace(128, c.d, c.V_sub, c.k)
+    for M in (14, 30, 48, 64, 96, 128):
+        _say("  rows of H:", M)
+        ids_g, lp_g = fr.fr_draft_topk(to_dev_bf16(H[:M]), W_g, idx_g, c.k, ws)
+        torch.cuda.synchronize()
+        sample = np.sort(np.random.default_rng(M).choice(M, size=4, replace=False))
+        ids_o, lp_o, z_o = oracle.draft_topk(H[sample], W_o, idx_o, c.k, want_logits=True)
+        check_topk_against_oracle(ids_g.cpu().numpy()[sample], lp_g.cpu().numpy()[sample], z_o, idx_o,
+                                  ids_o, lp_o)
+
+
 def test_full_vocab_m64_sampled_rows():
     # the uncompressed head at M=64, the comparison point of the batched configuration
     c = CONFIGS["batched256"]
