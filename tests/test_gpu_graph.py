@@ -92,3 +92,41 @@ def test_draft_phase_replayed_from_a_graph_equals_the_eager_calls(fused):
         fr.fr_draft_topk(H_other, W_g, idx_g, k, ws)
         torch.cuda.synchronize()
     assert fr.fr_workspace_check(ws) is False
+
+
+@pytest.mark.parametrize("M", [40, 100, 200])
+def test_chunked_kernel_replayed_from_a_graph_equals_the_eager_call(M):
+    # the chunked kernel's single-launch merge (40 and 100 rows of H: result mailbox) and its
+    # slabs (200 rows: two launches), captured and replayed with other calls in between
+    _say("graph replay of the chunked kernel, rows of H:", M)
+    d, V, V_sub, k = 256, 6000, 3000, 10
+    W = make_weights(V, d, 1)
+    r, _ = zipf_ranking(V, 1.1, 10 ** 6, 1)
+    W_g, idx_g = fr.fr_build_subset(to_dev_bf16(W), to_dev_i32(r), V_sub)
+    ws = fr.new_workspace(M, d, V, k)
+    H = torch.zeros((M, d), dtype=torch.bfloat16, device="cuda")
+    ids = torch.empty((M, k), dtype=torch.int32, device="cuda")
+    lp = torch.empty((M, k), dtype=torch.float32, device="cuda")
+    want = []
+    for case in range(2):
+        H.copy_(to_dev_bf16(make_hidden(M, d, 500 + case)))
+        fr.fr_draft_topk(H, W_g, idx_g, k, ws, token_ids=ids, logp=lp)
+        torch.cuda.synchronize()
+        want.append((ids.cpu().numpy().copy(), lp.cpu().numpy().copy()))
+    assert not np.array_equal(want[0][0], want[1][0])
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        fr.fr_draft_topk(H, W_g, idx_g, k, ws, token_ids=ids, logp=lp)
+    torch.cuda.synchronize()
+    H_other = to_dev_bf16(make_hidden(10, d, 998))
+    for replay, case in enumerate([1, 0, 0, 1]):
+        H.copy_(to_dev_bf16(make_hidden(M, d, 500 + case)))
+        ids.zero_()
+        lp.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(ids.cpu().numpy(), want[case][0]), (replay, case)
+        assert np.array_equal(lp.cpu().numpy().view(np.uint32), want[case][1].view(np.uint32)), (replay, case)
+        fr.fr_draft_topk(H_other, W_g, idx_g, k, ws)
+        torch.cuda.synchronize()
+    assert fr.fr_workspace_check(ws) is False
