@@ -9,6 +9,15 @@ import numpy as np
 import torch
 
 LOGIT_TOL = 1e-2
+# What the arithmetic gives (fp32 accumulation of d <= 4096 exact products, fast exp/log in the
+# normaliser): the full-size tests assert this tighter band beside the 1e-2 bar.
+TIGHT_TOL = 1e-4
+
+
+class ParityReport(float):
+    """The fraction of rows whose ids equal the oracle's, carrying the achieved errors."""
+    logp_err = 0.0     # max |logp_gpu - (z*_oracle[id] - logZ_oracle)| over all returned entries
+
 
 
 def to_dev_bf16(bits: np.ndarray) -> torch.Tensor:
@@ -25,16 +34,19 @@ def bits_of(t: torch.Tensor) -> np.ndarray:
 
 
 def check_topk_against_oracle(ids_g, logp_g, z_star, idx_map, ids_o, logp_o, tol=LOGIT_TOL,
-                              exact=False):
+                              exact=False, logp_tight=None):
     """ids_g/logp_g: GPU output [M,k]; z_star: oracle fp32 logits [M,rows];
     idx_map: position -> id (None = identity); ids_o/logp_o: oracle output.
-    Returns the fraction of rows whose ids match the oracle exactly."""
+    Returns the fraction of rows whose ids match the oracle exactly (a ParityReport: its
+    logp_err is the largest log-probability error seen); with logp_tight, that error must
+    also stay below logp_tight."""
     M, k = ids_g.shape
     rows = z_star.shape[1]
     ids_of_pos = np.arange(rows, dtype=np.int64) if idx_map is None else idx_map.astype(np.int64)
     pos_of_id = {}
     exact_rows = 0
     lz = None
+    logp_err = 0.0
     for m in range(M):
         if exact:
             assert np.array_equal(ids_g[m], ids_o[m]), (m, ids_g[m], ids_o[m])
@@ -53,8 +65,14 @@ def check_topk_against_oracle(ids_g, logp_g, z_star, idx_map, ids_o, logp_o, tol
         assert np.all(zg >= zo[-1] - tol), (m, zg, zo[-1])
         # (4) log-probabilities of the returned tokens
         lz = float(zo[0]) - float(logp_o[m, 0])   # oracle's log Z of this row
-        assert np.max(np.abs(logp_g[m].astype(np.float64) - (zg - lz))) <= tol, (m, logp_g[m], zg - lz)
+        err = float(np.max(np.abs(logp_g[m].astype(np.float64) - (zg - lz))))
+        assert err <= tol, (m, logp_g[m], zg - lz)
+        if logp_tight is not None:
+            assert err < logp_tight, (m, err, logp_g[m], zg - lz)
+        logp_err = max(logp_err, err)
         # (5) the GPU's own order
         assert np.all(np.diff(logp_g[m]) <= 0), (m, logp_g[m])
         exact_rows += int(np.array_equal(ids_g[m], ids_o[m]))
-    return exact_rows / M
+    report = ParityReport(exact_rows / M)
+    report.logp_err = logp_err
+    return report

@@ -181,3 +181,64 @@ def test_six_fused_steps_equal_six_unfused_steps():
         out.append([t.cpu().numpy() for t in hist + list(sel)])
     for a, b in zip(*out):
         assert np.array_equal(a.view(np.uint8), b.view(np.uint8))
+
+
+@pytest.mark.parametrize("M,k,width,V_sub,off,d", [(1, 10, 10, 2048, 0, 256), (10, 10, 10, 2048, 10, 256),
+                                                   (16, 16, 50, 3000, 7, 256), (10, 10, 10, 32768, 10, 4096),
+                                                   (10, 20, 10, 2048, 0, 256), (20, 10, 10, 2048, 0, 256)])
+def test_fused_draft_step_against_the_oracle(M, k, width, V_sub, off, d):
+    # fr_draft_step against oracle.draft_topk followed by oracle.beam_expand, with nothing of
+    # the library in between: tokens and parents bit for bit, scores inside the band of the
+    # log-probabilities (the head's logp differs from the oracle's in the last bits, and the
+    # cumulative score is one fp32 addition on top), next nodes equal except at near ties of
+    # the oracle's own scores.  The last-but-two case is the benchmark's shape.
+    from parity_utils import TIGHT_TOL, to_dev_bf16, to_dev_i32
+    from synth import make_hidden, make_weights, zipf_ranking
+    _say("fused draft step vs oracle", M, k, width, V_sub, off, d)
+    V = 8192 if d == 256 else 40000
+    W = make_weights(V, d, 3)
+    r, _ = zipf_ranking(V, 1.1, 10 ** 6, 3)
+    H = make_hidden(M, d, 300 + M)
+    rng = np.random.default_rng([20250214, 103, M, k])
+    node_score = (-rng.integers(0, 8, size=M) / 2).astype(np.float32)
+    node_hist = rng.integers(-1, max(off, 1), size=M).astype(np.int32)
+    n = off + M * k
+    W_o, idx_o = oracle.build_subset(W, r, V_sub)
+    ids_o, lp_o, z_o = oracle.draft_topk(H, W_o, idx_o, k, want_logits=True)
+    hs_o, ht_o, hp_o = np.full(n, 7.0, np.float32), np.full(n, 7, np.int32), np.full(n, 7, np.int32)
+    ns_o, nt_o, nh_o = oracle.beam_expand(lp_o, ids_o, node_score, node_hist, width, hs_o, ht_o, hp_o, off)
+
+    W_g, idx_g = fr.fr_build_subset(to_dev_bf16(W), to_dev_i32(r), V_sub)
+    ws = fr.new_workspace(M, d, V, k)
+    hist_g = [_dev(np.full(n, 7.0, np.float32)), _dev(np.full(n, 7, np.int32)), _dev(np.full(n, 7, np.int32))]
+    ids_g, lp_g, ns_g, nt_g, nh_g = fr.fr_draft_step(to_dev_bf16(H), W_g, idx_g, k, _dev(node_score), _dev(node_hist),
+                                                     width, *hist_g, off, ws)
+    torch.cuda.synchronize()
+    ids_g, lp_g = ids_g.cpu().numpy(), lp_g.cpu().numpy()
+    hs_g, ht_g, hp_g = (t.cpu().numpy() for t in hist_g)
+    ns_g, nt_g, nh_g = ns_g.cpu().numpy(), nt_g.cpu().numpy(), nh_g.cpu().numpy()
+    # the head's own outputs
+    same_ids = np.array_equal(ids_g, ids_o)
+    if not same_ids:     # only a near tie of two logits may reorder candidates
+        pos = {int(t): i for i, t in enumerate(idx_o)}
+        for m, j in zip(*np.nonzero(ids_g != ids_o)):
+            assert abs(z_o[m, pos[int(ids_g[m, j])]] - z_o[m, pos[int(ids_o[m, j])]]) < 1e-2
+    assert np.array_equal(hs_g[:off], hs_o[:off]) and np.array_equal(ht_g[:off], ht_o[:off])   # untouched
+    assert np.array_equal(hp_g, hp_o)                     # parents never depend on the arithmetic
+    assert np.array_equal(ht_g[off:], ids_g.reshape(-1))  # the history holds what the head returned
+    if same_ids:
+        assert np.array_equal(ht_g, ht_o)
+        assert float(np.max(np.abs(lp_g - lp_o))) < TIGHT_TOL
+        assert float(np.max(np.abs(hs_g[off:] - hs_o[off:]))) < TIGHT_TOL
+        # next nodes: the oracle's choice, except where its own scores at the two places tie closely
+        for j in range(width):
+            if nh_g[j] != nh_o[j]:
+                assert abs(float(hs_o[nh_g[j]]) - float(hs_o[nh_o[j]])) < 2 * TIGHT_TOL, (j, nh_g[j], nh_o[j])
+            assert nt_g[j] == ht_g[nh_g[j]] and ns_g[j] == hs_g[nh_g[j]]
+        assert len(set(int(x) for x in nh_g)) == width
+    # and the GPU's expansion is exactly the oracle's expansion of the GPU head's outputs
+    hs2, ht2, hp2 = np.full(n, 7.0, np.float32), np.full(n, 7, np.int32), np.full(n, 7, np.int32)
+    ns2, nt2, nh2 = oracle.beam_expand(lp_g, ids_g, node_score, node_hist, width, hs2, ht2, hp2, off)
+    assert np.array_equal(_bits(hs_g), _bits(hs2)) and np.array_equal(ht_g, ht2)
+    assert np.array_equal(_bits(ns_g), _bits(ns2)) and np.array_equal(nt_g, nt2) and np.array_equal(nh_g, nh2)
+    assert fr.fr_workspace_check(ws) is False
