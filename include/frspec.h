@@ -12,7 +12,10 @@
  *
  * Conventions common to every call
  *   - All data pointers are DEVICE pointers into memory owned by the caller.
- *     The library allocates nothing, frees nothing and keeps no global state.
+ *     The library allocates nothing and frees nothing.  Per-call state lives in the
+ *     caller's workspace; what the library itself keeps, per device and for the life of
+ *     the process, is the result of a one-time set-up (number of compute units, raised
+ *     LDS limits of its kernels): see fr_init.
  *   - bf16 tensors are row-major arrays of 16-bit patterns, 16-byte aligned.
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
  *     default stream) and the call returns without synchronising.  Outputs
@@ -45,6 +48,17 @@ typedef void *fr_stream;
 
 /* Human-readable text for a status code; never NULL; static storage. */
 const char *fr_strerror(fr_status status);
+
+/*
+ * One-time set-up of the CURRENT device: queries it and raises the LDS limit of every kernel
+ * build, so that afterwards a call only ever launches kernels.  Thread-safe and idempotent.
+ * Every entry point that launches performs the same set-up by itself the first time it runs
+ * on a device; that first call must not happen while the stream is being captured into a
+ * graph.  A program that captures calls fr_init() once per device beforehand (Section 3.1 of
+ * the paper: everything the drafting loop needs is prepared in advance).
+ * Returns FR_ERR_HIP if the runtime refuses a query.
+ */
+fr_status fr_init(void);
 
 /*
  * Eq. 3:  W_sub[i, :] = W_full[freq_ranked_ids[i], :]  and  idx_map[i] = freq_ranked_ids[i]
@@ -90,9 +104,13 @@ fr_status fr_workspace_init(void *workspace, size_t workspace_bytes, fr_stream s
  * Reads the workspace's sticky time-out word.  The single-launch kernels wait, inside the
  * launch, for partial results of other workgroups; every such wait is bounded, and a wait that
  * ever ran out (only possible if workgroups of one launch could not make progress for about a
- * second, or if the workspace was not prepared) sets the word and lets the call finish with
- * meaningless outputs.  *timed_out receives 0 or 1.  Synchronous: copies 4 bytes to the host
- * and waits for everything queued on `stream` before it.  fr_workspace_init clears the word.
+ * second, or if the workspace was not prepared) sets the word; the rows of the outputs whose
+ * merge gave up hold "no result" (token id INT32_MAX, logp -inf; for fr_draft_step also no
+ * next nodes: score -inf, token INT32_MAX, history index -1).  *timed_out receives 0 or 1.
+ * Synchronous: copies 4 bytes to the host and waits for everything queued on `stream` before
+ * it.  Once the word is set the workspace may still hold partial results of the abandoned
+ * call: prepare it again with fr_workspace_init (which also clears the word) before its next
+ * use.
  */
 fr_status fr_workspace_check(const void *workspace, size_t workspace_bytes, int32_t *timed_out,
                              fr_stream stream);
@@ -209,36 +227,6 @@ fr_status fr_tree_select(const float *hist_score, const int32_t *hist_token,
                          uint8_t *tree_mask, fr_stream stream);
 
 /*
- * Kernel-selection knobs for measurements and for tests that force one code path.
- * A zero in any field means "library default".
- */
-typedef struct fr_tuning {
-    int32_t path;        /* 3 = skinny kernel (M <= 16), products on the matrix cores (default),
-                            1 = skinny kernel, products on the vector ALUs (bf16 dot2),
-                            2 = chunked matrix-core kernel (any M) */
-    int32_t two_launch;  /* 1 = merge the per-workgroup partials in a second launch instead
-                            of inside the same launch */
-    int32_t variant;     /* skinny kernel build variant, 1-based (waves x pipeline depth x unit) */
-    int32_t ksplit;      /* waves that share one 16-row tile along d (1, 2, 4, 8) */
-    int32_t grid;        /* number of workgroups (<= 512) */
-    int32_t stream_only; /* 1 = measurement only: run the contraction and drop the logits
-                            (no softmax, no top-k; token_ids / logp are left untouched) */
-    int32_t skew;        /* > 0: rows that every odd workgroup hands to its even neighbour when each
-                            workgroup has exactly one pass (experimental die balancing; off by default) */
-    int32_t no_mailbox;  /* 1 = the chunked kernel merges through the plain partial arrays and the
-                            arrival counter even where the result mailbox applies */
-    void *trace;         /* optional device buffer of 8 * 512 int64: every workgroup of a
-                            contraction kernel records 100 MHz timestamps of its phases there */
-} fr_tuning;
-
-/* fr_draft_topk with explicit knobs (tuning == NULL behaves exactly like fr_draft_topk). */
-fr_status fr_draft_topk_tuned(const void *H, int64_t M, int64_t d,
-                              const void *W_sub, const int32_t *idx_map, int64_t V_sub,
-                              int32_t k, int32_t *token_ids, float *logp,
-                              void *workspace, size_t workspace_bytes, fr_stream stream,
-                              const fr_tuning *tuning);
-
-/*
  * fr_draft_topk for hidden states that sit in several blocks of memory (several draft heads
  * evaluated against one W_sub, as when the method is applied to Medusa-style heads, Section
  * 4.5): block b holds rows_per_block rows, bf16 [rows_per_block, d] row-major; row
@@ -266,7 +254,7 @@ fr_status fr_draft_topk_multi(const void *const *H_blocks, int32_t n_blocks, int
  *   fr_build_subset_tiled  as fr_build_subset, writing W_tiled; a row whose id is outside
  *                          [0, V) is zero, idx_map = -1, *dev_error_flag set
  *   fr_draft_topk_tiled    as fr_draft_topk, reading W_tiled; M <= 16 (FR_ERR_UNSUPPORTED
- *                          beyond); `tuning` may be NULL
+ *                          beyond)
  */
 size_t fr_tiled_bytes(int64_t V_sub, int64_t d);
 fr_status fr_build_subset_tiled(const void *W_full, int64_t V, int64_t d,
@@ -275,8 +263,7 @@ fr_status fr_build_subset_tiled(const void *W_full, int64_t V, int64_t d,
 fr_status fr_draft_topk_tiled(const void *H, int64_t M, int64_t d, const void *W_tiled,
                               const int32_t *idx_map, int64_t V_sub, int32_t k,
                               int32_t *token_ids, float *logp, void *workspace,
-                              size_t workspace_bytes, fr_stream stream,
-                              const fr_tuning *tuning);
+                              size_t workspace_bytes, fr_stream stream);
 
 
 /*
@@ -294,15 +281,6 @@ fr_status fr_count_tokens(const int32_t *tokens, int64_t n_tokens, int64_t V, in
                           int32_t *dev_error_flag, fr_stream stream);
 fr_status fr_rank_tokens(const int64_t *counts, int64_t V, int32_t *freq_ranked_ids,
                          fr_stream stream);
-
-/*
- * Bandwidth calibration kernels: a plain copy and a plain read of `bytes` bytes
- * (multiple of 16), used to scale hardware counters and to report what a trivial
- * streaming kernel achieves on the same machine.  `sink` receives one 16-byte value
- * (only so that the read cannot be optimised away).
- */
-fr_status fr_calib_copy(void *dst, const void *src, size_t bytes, fr_stream stream);
-fr_status fr_calib_read(const void *src, size_t bytes, void *sink, fr_stream stream);
 
 /* Library version, major*100 + minor. */
 int fr_version(void);

@@ -19,12 +19,16 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "frspec_oracle.c")
 _SRCS = [_SRC, os.path.join(_HERE, "beam_oracle.c"), os.path.join(_HERE, "freq_oracle.c")]
 _LIB = os.path.join(_HERE, "liboracle.so")
+# A differently built copy of the same sources (the sanitizer build of the test suite) can stand in.
+_LIB_OVERRIDE = os.environ.get("FRSPEC_ORACLE_SO")
 
 _lib = None
 
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (-O2, OpenMP, no fast-math).  Returns the .so path."""
+    if _LIB_OVERRIDE and not force:
+        return _LIB_OVERRIDE
     stale = not os.path.exists(_LIB) or any(os.path.getmtime(_LIB) < os.path.getmtime(src) for src in _SRCS)
     if force or stale:
         cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-Wextra",
@@ -36,8 +40,7 @@ def build(force: bool = False) -> str:
 def _load():
     global _lib
     if _lib is None:
-        build()
-        lib = ctypes.CDLL(_LIB)
+        lib = ctypes.CDLL(build())
         i64, i32, vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p
         lib.oracle_build_subset.argtypes = [vp, i64, i64, vp, i64, vp, vp]
         lib.oracle_logits_f32.argtypes = [vp, i64, i64, vp, i64, vp]

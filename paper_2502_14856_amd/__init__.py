@@ -21,6 +21,7 @@ from .binding import (  # noqa: F401
     fr_draft_topk_multi,
     fr_draft_topk_tiled,
     fr_full_topk,
+    fr_init,
     fr_rank_tokens,
     fr_strerror,
     fr_tiled_bytes,

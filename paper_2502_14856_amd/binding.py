@@ -25,11 +25,12 @@ class FrSpecError(RuntimeError):
 
 
 class Tuning(ctypes.Structure):
-    """Mirror of ``fr_tuning``; zero fields mean library default."""
+    """Mirror of ``fr_tuning`` (include/frspec_dev.h); zero fields mean library default."""
     _fields_ = [("path", ctypes.c_int32), ("two_launch", ctypes.c_int32),
                 ("variant", ctypes.c_int32), ("ksplit", ctypes.c_int32),
                 ("grid", ctypes.c_int32), ("stream_only", ctypes.c_int32),
                 ("skew", ctypes.c_int32), ("no_mailbox", ctypes.c_int32),
+                ("spin_limit", ctypes.c_int32), ("reserved", ctypes.c_int32),
                 ("trace", ctypes.c_void_p)]
 
 
@@ -71,8 +72,10 @@ def lib():
         L.fr_tiled_bytes.argtypes = [i64, i64]
         L.fr_tiled_bytes.restype = sz
         L.fr_build_subset_tiled.argtypes = [vp, i64, i64, vp, i64, vp, vp, vp, vp]
-        L.fr_draft_topk_tiled.argtypes = [vp, i64, i64, vp, vp, i64, i32, vp, vp, vp, sz, vp,
-                                          ctypes.POINTER(Tuning)]
+        L.fr_draft_topk_tiled.argtypes = [vp, i64, i64, vp, vp, i64, i32, vp, vp, vp, sz, vp]
+        L.fr_draft_topk_tiled_tuned.argtypes = [vp, i64, i64, vp, vp, i64, i32, vp, vp, vp, sz, vp,
+                                                ctypes.POINTER(Tuning)]
+        L.fr_init.argtypes = []
         L.fr_draft_step.argtypes = [vp, i64, i64, vp, vp, i64, i32, vp, vp, i32, vp, vp, vp, i64, vp, vp, vp, vp, vp,
                                     vp, sz, vp]
         L.fr_beam_expand.argtypes = [vp, vp, i64, i32, vp, vp, i32, vp, vp, vp, i64, vp, vp, vp, vp]
@@ -81,7 +84,7 @@ def lib():
         L.fr_calib_read.argtypes = [vp, sz, vp, vp]
         for name in ("fr_build_subset", "fr_workspace_init", "fr_workspace_check", "fr_draft_topk", "fr_draft_topk_tuned",
                      "fr_full_topk", "fr_draft_logits", "fr_beam_expand", "fr_tree_select", "fr_draft_step", "fr_draft_topk_multi", "fr_count_tokens", "fr_rank_tokens", "fr_build_subset_tiled",
-                     "fr_draft_topk_tiled", "fr_calib_copy",
+                     "fr_draft_topk_tiled", "fr_draft_topk_tiled_tuned", "fr_init", "fr_calib_copy",
                      "fr_calib_read"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -94,6 +97,11 @@ def fr_strerror(status: int) -> str:
 
 def fr_version() -> int:
     return int(lib().fr_version())
+
+
+def fr_init() -> None:
+    """One-time set-up of the current device (see frspec.h); needed before a stream capture."""
+    _check(lib().fr_init(), "fr_init")
 
 
 def _stream(stream):
@@ -311,10 +319,15 @@ def fr_draft_topk_tiled(H, W_tiled, idx_map, V_sub: int, k: int, workspace, toke
         token_ids = torch.empty((M, k), dtype=torch.int32, device=H.device)
     if logp is None:
         logp = torch.empty((M, k), dtype=torch.float32, device=H.device)
-    _check(lib().fr_draft_topk_tiled(_ptr(H), M, d, _ptr(W_tiled), _ptr(idx_map), V_sub, k, _ptr(token_ids),
-                                     _ptr(logp), _ptr(workspace), workspace.numel() * workspace.element_size(),
-                                     _stream(stream), ctypes.byref(tuning) if tuning is not None else None),
-           "fr_draft_topk_tiled")
+    ws_bytes = workspace.numel() * workspace.element_size()
+    if tuning is None:
+        st = lib().fr_draft_topk_tiled(_ptr(H), M, d, _ptr(W_tiled), _ptr(idx_map), V_sub, k, _ptr(token_ids),
+                                       _ptr(logp), _ptr(workspace), ws_bytes, _stream(stream))
+    else:
+        st = lib().fr_draft_topk_tiled_tuned(_ptr(H), M, d, _ptr(W_tiled), _ptr(idx_map), V_sub, k, _ptr(token_ids),
+                                             _ptr(logp), _ptr(workspace), ws_bytes, _stream(stream),
+                                             ctypes.byref(tuning))
+    _check(st, "fr_draft_topk_tiled")
     return token_ids, logp
 
 

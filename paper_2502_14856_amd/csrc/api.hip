@@ -1,23 +1,47 @@
 // C ABI of libfrspec: argument validation on the host, workspace carving, dispatch.
+#include <atomic>
 #include <mutex>
 
 #include "internal.hpp"
 
 namespace frspec {
 
-int device_cu_count() {
-    static std::mutex mu;
-    static int cached[64];
+namespace {
+constexpr int kMaxDevices = 64;
+struct DeviceSlot {
+    std::atomic<int> ready{0};
+    DeviceState state{};
+};
+DeviceSlot g_device[kMaxDevices];
+std::mutex g_setup_mutex;
+}  // namespace
+
+const DeviceState *device_state() {
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return -1;
-    std::lock_guard<std::mutex> lock(mu);
-    if (cached[dev] == 0) {
-        int n = 0;
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-            return -1;
-        cached[dev] = n;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return nullptr;
     }
-    return cached[dev];
+    DeviceSlot &slot = g_device[dev];
+    if (slot.ready.load(std::memory_order_acquire)) return &slot.state;
+    std::lock_guard<std::mutex> lock(g_setup_mutex);
+    if (slot.ready.load(std::memory_order_relaxed)) return &slot.state;
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    slot.state.cus = n;
+    if (prepare_skinny_kernels() != FR_OK || prepare_wide_kernels() != FR_OK || prepare_glue_kernels() != FR_OK ||
+        prepare_freq_kernels() != FR_OK)
+        return nullptr;
+    slot.ready.store(1, std::memory_order_release);
+    return &slot.state;
+}
+
+int device_cu_count() {
+    const DeviceState *st = device_state();
+    return st ? st->cus : -1;
 }
 
 namespace {
@@ -65,7 +89,8 @@ fr_status head_topk(const void *H, int64_t M, int64_t d, const void *W, const in
     const WorkspaceLayout wl(M, k);
     if (workspace_bytes < wl.total) return FR_ERR_WORKSPACE;
     if (tuning && (tuning->path < 0 || tuning->path > 3 || tuning->grid < 0 ||
-                   tuning->grid > kWorkspaceGridMax || tuning->variant < 0 || tuning->ksplit < 0))
+                   tuning->grid > kWorkspaceGridMax || tuning->variant < 0 || tuning->ksplit < 0 ||
+                   tuning->spin_limit < 0))
         return FR_ERR_INVALID_ARG;
 
     char *ws = static_cast<char *>(workspace);
@@ -157,7 +182,9 @@ const char *fr_strerror(fr_status status) {
     return "unknown status";
 }
 
-int fr_version(void) { return 100; }
+int fr_version(void) { return 101; }
+
+fr_status fr_init(void) { return device_state() ? FR_OK : FR_ERR_HIP; }
 
 fr_status fr_build_subset(const void *W_full, int64_t V, int64_t d, const int32_t *freq_ranked_ids,
                           int64_t V_sub, void *W_sub, int32_t *idx_map, int32_t *dev_error_flag,
@@ -188,8 +215,15 @@ fr_status fr_build_subset_tiled(const void *W_full, int64_t V, int64_t d, const 
 
 fr_status fr_draft_topk_tiled(const void *H, int64_t M, int64_t d, const void *W_tiled,
                               const int32_t *idx_map, int64_t V_sub, int32_t k, int32_t *token_ids,
-                              float *logp, void *workspace, size_t workspace_bytes, fr_stream stream,
-                              const fr_tuning *tuning) {
+                              float *logp, void *workspace, size_t workspace_bytes, fr_stream stream) {
+    return head_topk(H, M, d, W_tiled, idx_map, V_sub, k, token_ids, logp, workspace, workspace_bytes, stream,
+                     nullptr, true);
+}
+
+fr_status fr_draft_topk_tiled_tuned(const void *H, int64_t M, int64_t d, const void *W_tiled,
+                                    const int32_t *idx_map, int64_t V_sub, int32_t k, int32_t *token_ids,
+                                    float *logp, void *workspace, size_t workspace_bytes, fr_stream stream,
+                                    const fr_tuning *tuning) {
     return head_topk(H, M, d, W_tiled, idx_map, V_sub, k, token_ids, logp, workspace, workspace_bytes, stream,
                      tuning, true);
 }

@@ -117,12 +117,15 @@ struct Arrival {
  *
  * Every thread of a workgroup calls this after publishing its partials; `turn` is the
  * value read when the workgroup started.  Returns -1 in workgroups that do not merge
- * (they are finished), else r, after all G workgroups have arrived.  At most kMaxMergers
+ * (they are finished), else r, after all G workgroups have arrived; r | kWaitTimedOut if the
+ * wait was given up after `spin_limit` polls (the caller then reports "no result" for its rows).  At most kMaxMergers
  * workgroups ever wait, the workgroups they wait for need nothing from them, and a
  * waiting workgroup occupies one compute unit of many, so the wait cannot starve a
  * workgroup that has not been scheduled yet; it is bounded all the same.
  */
-__device__ __forceinline__ int arrive_and_wait(const Arrival &ar, unsigned turn, int G, int R, int *s_slot) {
+constexpr int kWaitTimedOut = 1 << 30;   // set in arrive_and_wait's result when its wait ran out
+__device__ __forceinline__ int arrive_and_wait(const Arrival &ar, unsigned turn, int G, int R, int *s_slot,
+                                               unsigned spin_limit) {
     wait_stores_done();
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -133,7 +136,7 @@ __device__ __forceinline__ int arrive_and_wait(const Arrival &ar, unsigned turn,
             __hip_atomic_store(ar.count + 32 * (turn ^ 1u), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(ar.parity, turn ^ 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        const int r = a < (unsigned)R ? (int)a : -1;
+        int r = a < (unsigned)R ? (int)a : -1;
         if (r >= 0) {
             auto poll = [mine]() { return __hip_atomic_load(mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
             unsigned q0 = poll(), q1 = poll(), q2 = poll(), q3 = poll();   // oldest first
@@ -144,8 +147,9 @@ __device__ __forceinline__ int arrive_and_wait(const Arrival &ar, unsigned turn,
                 q2 = q3;
                 q3 = poll();
                 __builtin_amdgcn_s_sleep(1);
-                if (++polls > kSpinLimit) {
+                if (++polls > spin_limit) {
                     __hip_atomic_store(ar.error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    r |= kWaitTimedOut;
                     break;
                 }
             }
@@ -154,6 +158,18 @@ __device__ __forceinline__ int arrive_and_wait(const Arrival &ar, unsigned turn,
     }
     __syncthreads();
     return *s_slot;
+}
+
+// "No result" for rows first, first + stride, ... of the outputs: what a merger writes when a
+// bounded wait ran out, so that a caller who ignores the sticky error word at least sees no
+// plausible-looking candidates.  One wavefront; k <= 64.
+__device__ __forceinline__ void write_no_result(int first, int stride, int M, int k, int *token_ids, float *logp) {
+    const int lane = lane_id();
+    for (int m = first; m < M; m += stride)
+        if (lane < k) {
+            token_ids[(size_t)m * k + lane] = INT_MAX;
+            logp[(size_t)m * k + lane] = kNegInf;
+        }
 }
 
 __device__ __forceinline__ int merger_count(int G, int M) {
@@ -874,6 +890,7 @@ struct alignas(16) MergeScratch {
     unsigned long long key[kWave];
     unsigned count;
     float logZ;
+    unsigned timed_out;   // a fetching wavefront gave up waiting for this row's records
 };
 
 // The general merge of a set of rows by one wavefront, kept out of line.
@@ -893,7 +910,7 @@ __device__ __noinline__ void final_merge_general(Partials P, int G, int first, i
 
 // One wavefront; keys: LDS, at least M * k + 2 entries, 16-byte aligned.
 __device__ __forceinline__ void expand_step_fused(const StepArgs &st, int M, int k, unsigned long long *keys,
-                                                  unsigned *error) {
+                                                  unsigned *error, unsigned spin_limit) {
     constexpr int CPL = kStepRows * kMailK / kWave;   // 4 candidates per lane at most
     const int lane = lane_id(), C = M * k;
     unsigned long long r[CPL];
@@ -916,9 +933,15 @@ __device__ __forceinline__ void expand_step_fused(const StepArgs &st, int M, int
                 again = true;
             }
         if (!__any(again)) break;
-        if (polls > kMailSpinLimit) {
+        if (polls > spin_limit) {
+            // given up: no next nodes, the history stays as it was
             if (lane == 0) __hip_atomic_store(error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            break;
+            for (int w = lane; w < st.width; w += kWave) {
+                st.next_score[w] = kNegInf;
+                st.next_token[w] = INT_MAX;
+                st.next_hist[w] = -1;
+            }
+            return;
         }
         __builtin_amdgcn_s_sleep(1);
     }
@@ -971,7 +994,7 @@ template <int NW = 4>   // fetching wavefronts: 4 or 8, at most the wavefronts o
 __device__ __forceinline__ void merge_rows_mailbox(const Mailbox &mb, const Partials &P, unsigned *error, int G,
                                                    int first, int stride, int M, int k, int *token_ids,
                                                    float *logp, MergeScratch *ms, SelectScratch *sc,
-                                                   unsigned long long *step_rec) {
+                                                   unsigned long long *step_rec, unsigned spin_limit) {
     constexpr int HPL = 4;                      // G <= 256
     static_assert(NW == 4 || NW == 8, "list positions are dealt out evenly");
     constexpr int TPW = kMailK / NW;            // list positions per fetching wavefront
@@ -980,7 +1003,10 @@ __device__ __forceinline__ void merge_rows_mailbox(const Mailbox &mb, const Part
     for (int m = first; m < M; m += stride) {
         if (wave == 0) {
             ms->key[lane] = 0ull;
-            if (lane == 0) ms->count = 0u;
+            if (lane == 0) {
+                ms->count = 0u;
+                ms->timed_out = 0u;
+            }
         }
         __syncthreads();
         unsigned long long ent[TPW][HPL], head[HPL], stt[HPL];
@@ -1024,8 +1050,11 @@ __device__ __forceinline__ void merge_rows_mailbox(const Mailbox &mb, const Part
                     }
                 }
                 if (!__any(again)) break;
-                if (polls > kMailSpinLimit) {
-                    if (lane == 0) __hip_atomic_store(error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (polls > spin_limit) {
+                    if (lane == 0) {
+                        __hip_atomic_store(error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        ms->timed_out = 1u;
+                    }
                     break;
                 }
                 __builtin_amdgcn_s_sleep(1);
@@ -1095,6 +1124,16 @@ __device__ __forceinline__ void merge_rows_mailbox(const Mailbox &mb, const Part
             }
         }
         __syncthreads();
+        if (ms->timed_out != 0u) {
+            // A wait ran out: this row has no result (and the records that may still arrive stay
+            // in the mailbox: the workspace has to be prepared again before its next use).
+            if (wave == 0) {
+                write_no_result(m, M, M, k, token_ids, logp);
+                if (step_rec && lane < k) publish(step_rec + m * kMailK + lane, mail_pack(kNegInf, (unsigned)INT_MAX));
+            }
+            __syncthreads();   // (every wavefront has read the flag before the next row resets it)
+            continue;
+        }
 
         // Every fetching wavefront has its records in registers: they are emptied for the next
         // call by all wavefronts but the first, which ranks and writes the outputs meanwhile

@@ -90,19 +90,19 @@ __global__ __launch_bounds__(kRankThreads) void rank_kernel(const long long *__r
 
 }  // namespace
 
+fr_status prepare_freq_kernels() {
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(count_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            kSlice * 4) != hipSuccess) {
+        (void)hipGetLastError();
+        return FR_ERR_HIP;
+    }
+    return FR_OK;
+}
+
 fr_status launch_count_tokens(const int *tokens, long long n, int V, unsigned long long *counts, int *flag,
                               hipStream_t s) {
     const int cus = device_cu_count();
     if (cus <= 0) return FR_ERR_HIP;
-    static bool attr_done = false;
-    if (!attr_done) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(count_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kSlice * 4) != hipSuccess) {
-            (void)hipGetLastError();
-            return FR_ERR_HIP;
-        }
-        attr_done = true;
-    }
     long long blocks = (n / 4 + kCountThreads - 1) / kCountThreads;
     if (blocks > cus) blocks = cus;
     if (blocks < 1) blocks = 1;

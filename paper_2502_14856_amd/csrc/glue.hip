@@ -169,19 +169,21 @@ fr_status launch_beam_expand(const float *logp, const int *token_ids, int C, int
     return hip_status(hipGetLastError());
 }
 
+// up to 80 KiB + 16 B of dynamic LDS: above the default limit
+fr_status prepare_glue_kernels() {
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(tree_select_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024) != hipSuccess) {
+        (void)hipGetLastError();
+        return FR_ERR_HIP;
+    }
+    return FR_OK;
+}
+
 fr_status launch_tree_select(const float *hist_score, const int *hist_token, const int *hist_parent, int N, int K,
                              int *sel_index, int *sel_token, int *sel_parent, int *sel_depth,
                              unsigned char *tree_mask, hipStream_t s) {
     const size_t lds = ((size_t)((N + 2) & ~1)) * sizeof(unsigned long long) + 3 * (size_t)N * sizeof(int);
-    static bool attr_done = false;   // up to 80 KiB + 16 B of dynamic LDS: above the default limit
-    if (!attr_done) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(tree_select_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024) != hipSuccess) {
-            (void)hipGetLastError();
-            return FR_ERR_HIP;
-        }
-        attr_done = true;
-    }
+    if (!device_state()) return FR_ERR_HIP;   // (the per-device set-up raised this kernel's LDS limit)
     hipLaunchKernelGGL(tree_select_kernel, dim3(1), dim3(kGlueThreads), lds, s, hist_score, hist_token,
                        hist_parent, N, K, sel_index, sel_token, sel_parent, sel_depth, tree_mask);
     return hip_status(hipGetLastError());

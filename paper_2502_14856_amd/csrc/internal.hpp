@@ -5,7 +5,7 @@
 #include <stddef.h>
 #include <stdint.h>
 
-#include "../../include/frspec.h"
+#include "../../include/frspec_dev.h"
 
 namespace frspec {
 
@@ -71,8 +71,22 @@ constexpr int kWorkspaceGridMax = 512;   // partial slots reserved per row of H
 constexpr int kMatrixPathMaxM = 256;     // rows of H per matrix-core launch
 constexpr int kSkinnyMaxM = 16;          // rows of H the vector-ALU kernel covers
 
-// Number of compute units of the current device (cached per device); <= 0 on error.
+// What the library keeps per device, filled by the per-device set-up: fr_init(), or the first
+// call of any entry point that launches on that device.  The set-up queries the device, raises
+// the dynamic LDS limit of every kernel build (so that no launch ever changes a function
+// attribute) and is thread-safe.
+struct DeviceState {
+    int cus;   // compute units
+};
+// State of the current device, after its set-up; nullptr if the set-up failed.
+const DeviceState *device_state();
+// Number of compute units of the current device; <= 0 on error.
 int device_cu_count();
+// The parts of the set-up that live with their kernels.
+fr_status prepare_skinny_kernels();
+fr_status prepare_wide_kernels();
+fr_status prepare_glue_kernels();
+fr_status prepare_freq_kernels();
 
 // skinny.hip: kernel for M <= 16 with all of H in LDS.  Returns FR_ERR_UNSUPPORTED if H does not fit.
 fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hipStream_t s);

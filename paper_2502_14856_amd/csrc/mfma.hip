@@ -43,6 +43,7 @@ struct WideArgs {
     int steps;    // ceil(d8 / 16)
     int passes;
     int sink;
+    unsigned spin_limit;  // polls after which a wait for other workgroups is given up (0: the default)
     Partials part;
     Mailbox mail;
     int mailbox;  // the results go through the mailbox records (single launch, k <= 16, M <= 128)
@@ -385,7 +386,7 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
             if (gidx < G - R) return;
             stamp(4);
             merge_rows_mailbox<(WAVES >= 8 ? 8 : 4)>(mb, part, a.ticket + 1, G, gidx - (G - R), R, a.M, a.k, a.token_ids, a.logp,
-                               &s_merge, &s_select[0], nullptr);
+                               &s_merge, &s_select[0], nullptr, a.spin_limit ? a.spin_limit : kMailSpinLimit);
             __syncthreads();
             stamp(5);
         }
@@ -394,9 +395,13 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
     if (a.sink == (int)Sink::kPartialsOnly) return;
 
     const int R = merger_count(G, a.M);
-    const int r = arrive_and_wait(ar, (unsigned)__builtin_amdgcn_readfirstlane((int)turn), G, R, &s_slot);
+    const int r = arrive_and_wait(ar, (unsigned)__builtin_amdgcn_readfirstlane((int)turn), G, R, &s_slot,
+                                  a.spin_limit ? a.spin_limit : kSpinLimit);
     if (r < 0) return;
-    final_merge_all(part, G, r + R * wave, R * WAVES, a.M, a.k, a.token_ids, a.logp, &s_select[wave]);
+    if (r & kWaitTimedOut)
+        write_no_result((r & ~kWaitTimedOut) + R * wave, R * WAVES, a.M, a.k, a.token_ids, a.logp);
+    else
+        final_merge_all(part, G, r + R * wave, R * WAVES, a.M, a.k, a.token_ids, a.logp, &s_select[wave]);
 }
 
 constexpr int kLdsBudget = 160 * 1024;
@@ -416,24 +421,35 @@ const Build *build_for(int M, int k) {
     return nullptr;
 }
 
-template <int MT16, int RB, int WAVES, int DEPTH, int HCH>
-fr_status launch_one(const WideArgs &a, int grid, int lds, hipStream_t s) {
-    auto kern = wide_kernel<MT16, RB, WAVES, DEPTH, HCH>;
-    static bool attr_done = false;
-    if (!attr_done) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+typedef void (*WideKernel)(WideArgs);
+constexpr int kWideWaves = 8;
+
+// the build for `mt16` tiles of 16 rows of H
+WideKernel select_kernel(int mt16) {
+    switch (mt16) {
+        case 1: return wide_kernel<1, 1, kWideWaves, 4, 8>;
+        case 2: return wide_kernel<2, 1, kWideWaves, 4, 8>;
+        case 3: return wide_kernel<3, 1, kWideWaves, 4, 8>;
+        case 4: return wide_kernel<4, 1, kWideWaves, 4, 4>;
+        case 6: return wide_kernel<6, 1, kWideWaves, 4, 4>;
+        case 8: return wide_kernel<8, 1, kWideWaves, 4, 2>;
+    }
+    return nullptr;
+}
+
+}  // namespace
+
+// Raises the dynamic LDS limit of every build on the current device (per-device set-up).
+fr_status prepare_wide_kernels() {
+    for (const Build &b : kBuilds)
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(select_kernel(b.mt16)),
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                 kLdsBudget - kStaticLdsReserve) != hipSuccess) {
             (void)hipGetLastError();
             return FR_ERR_HIP;
         }
-        attr_done = true;
-    }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(WAVES * kWave), lds, s, a);
-    return hip_status(hipGetLastError());
+    return FR_OK;
 }
-
-}  // namespace
 
 // Largest slab of H rows (multiple of 16, <= 128) whose per-row state fits LDS for this k.
 int mfma_max_rows(int k) {
@@ -474,6 +490,7 @@ fr_status launch_mfma(const HeadProblem &p, Sink sink, const fr_tuning *t, hipSt
     a.z_out = p.z_out;
     a.z_ld = p.z_ld;
     a.trace = t ? static_cast<long long *>(t->trace) : nullptr;
+    a.spin_limit = t && t->spin_limit > 0 ? (unsigned)t->spin_limit : 0u;
 
     int grid = cus < a.passes ? cus : a.passes;   // one persistent workgroup per compute unit
     if (t && t->grid > 0) grid = t->grid < a.passes ? t->grid : a.passes;
@@ -485,15 +502,10 @@ fr_status launch_mfma(const HeadProblem &p, Sink sink, const fr_tuning *t, hipSt
     a.mailbox = sink == Sink::kFusedTopk && p.k <= kMailK && p.M <= kMailRows && grid <= 4 * kWave &&
                 !(t && t->no_mailbox);
 
-    fr_status st = FR_ERR_UNSUPPORTED;
-    switch (b->mt16) {
-        case 1: st = launch_one<1, 1, 8, 4, 8>(a, grid, lds, s); break;
-        case 2: st = launch_one<2, 1, 8, 4, 8>(a, grid, lds, s); break;
-        case 3: st = launch_one<3, 1, 8, 4, 8>(a, grid, lds, s); break;
-        case 4: st = launch_one<4, 1, 8, 4, 4>(a, grid, lds, s); break;
-        case 6: st = launch_one<6, 1, 8, 4, 4>(a, grid, lds, s); break;
-        case 8: st = launch_one<8, 1, 8, 4, 2>(a, grid, lds, s); break;
-    }
+    const WideKernel kern = select_kernel(b->mt16);
+    if (!kern) return FR_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kWideWaves * kWave), lds, s, a);
+    const fr_status st = hip_status(hipGetLastError());
     if (st != FR_OK) return st;
     if (sink == Sink::kPartialsOnly) return launch_merge(p, grid, s);
     return FR_OK;

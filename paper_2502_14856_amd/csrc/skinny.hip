@@ -62,6 +62,7 @@ struct SkinnyArgs {
     int steps_per_split;  // ceil(steps / KS)
     int passes;           // ceil(V_rows / rows per pass)
     int sink;
+    unsigned spin_limit;  // polls after which a wait for other workgroups is given up (0: the default)
     Partials part;
     Mailbox mail;
     StepArgs step;
@@ -512,16 +513,21 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
         const int r = (top - b) / spread;
         if (b > top || b % spread != 0 || r >= R) return;
         stamp(4);
+        const unsigned spin = a.spin_limit ? a.spin_limit : kMailSpinLimit;
         merge_rows_mailbox<(WAVES >= 8 ? 8 : 4)>(a.mail, part, a.ticket + 1, G, r, R, a.M, a.k, a.token_ids, a.logp, &s_merge,
-                           &s_select[0], a.step.rec);
+                           &s_select[0], a.step.rec, spin);
         // the first merger also runs the beam-search expansion of the step, if one was asked for
         if (a.step.rec && r == 0 && wave == 0)
-            expand_step_fused(a.step, a.M, a.k, reinterpret_cast<unsigned long long *>(s_select), a.ticket + 1);
+            expand_step_fused(a.step, a.M, a.k, reinterpret_cast<unsigned long long *>(s_select), a.ticket + 1, spin);
     } else {
-        const int r = arrive_and_wait(ar, (unsigned)__builtin_amdgcn_readfirstlane((int)turn), G, R, &s_slot);
+        const int r = arrive_and_wait(ar, (unsigned)__builtin_amdgcn_readfirstlane((int)turn), G, R, &s_slot,
+                                      a.spin_limit ? a.spin_limit : kSpinLimit);
         stamp(4);
         if (r < 0) return;
-        final_merge_general(part, G, r + R * wave, R * WAVES, a.M, a.k, a.token_ids, a.logp, &s_select[wave]);
+        if (r & kWaitTimedOut)
+            write_no_result((r & ~kWaitTimedOut) + R * wave, R * WAVES, a.M, a.k, a.token_ids, a.logp);
+        else
+            final_merge_general(part, G, r + R * wave, R * WAVES, a.M, a.k, a.token_ids, a.logp, &s_select[wave]);
     }
     __syncthreads();
     stamp(5);
@@ -540,37 +546,22 @@ int bucket_for(int M) {
     return -1;
 }
 
-template <int MT, int WAVES, int DEPTH, bool MFMA, bool TILED = false, bool SKEW = false, int HR = 16>
-fr_status launch_one(const SkinnyArgs &a, int grid, int lds, hipStream_t s) {
-    auto kern = skinny_kernel<MT, WAVES, DEPTH, MFMA, TILED, SKEW, HR>;
-    static bool attr_done = false;   // raising the dynamic LDS limit is idempotent
-    if (!attr_done) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kLdsBudget - kStaticLdsReserve) != hipSuccess) {
-            (void)hipGetLastError();
-            return FR_ERR_HIP;
-        }
-        attr_done = true;
-    }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(WAVES * kWave), lds, s, a);
-    return hip_status(hipGetLastError());
-}
+typedef void (*SkinnyKernel)(SkinnyArgs);
 
 // The dot-product variant is compiled per width of its register tile.
 template <int WAVES, int DEPTH>
-fr_status launch_dot(int MT, const SkinnyArgs &a, int grid, int lds, hipStream_t s) {
+SkinnyKernel dot_kernel(int MT) {
     switch (MT) {
-        case 1: return launch_one<1, WAVES, DEPTH, false>(a, grid, lds, s);
-        case 2: return launch_one<2, WAVES, DEPTH, false>(a, grid, lds, s);
-        case 4: return launch_one<4, WAVES, DEPTH, false>(a, grid, lds, s);
-        case 6: return launch_one<6, WAVES, DEPTH, false>(a, grid, lds, s);
-        case 8: return launch_one<8, WAVES, DEPTH, false>(a, grid, lds, s);
-        case 10: return launch_one<10, WAVES, DEPTH, false>(a, grid, lds, s);
-        case 12: return launch_one<12, WAVES, DEPTH, false>(a, grid, lds, s);
-        case 16: return launch_one<16, WAVES, DEPTH, false>(a, grid, lds, s);
+        case 1: return skinny_kernel<1, WAVES, DEPTH, false>;
+        case 2: return skinny_kernel<2, WAVES, DEPTH, false>;
+        case 4: return skinny_kernel<4, WAVES, DEPTH, false>;
+        case 6: return skinny_kernel<6, WAVES, DEPTH, false>;
+        case 8: return skinny_kernel<8, WAVES, DEPTH, false>;
+        case 10: return skinny_kernel<10, WAVES, DEPTH, false>;
+        case 12: return skinny_kernel<12, WAVES, DEPTH, false>;
+        case 16: return skinny_kernel<16, WAVES, DEPTH, false>;
     }
-    return FR_ERR_UNSUPPORTED;
+    return nullptr;
 }
 
 struct Variant {
@@ -603,6 +594,30 @@ constexpr int kSkewDefaultRows = 4;
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 constexpr int kMfmaTile = 16;   // the matrix-core variant is compiled once, for up to 16 rows
 
+// The kernel build behind a variant, for M rows of H (MT: width of the vector-ALU tile).
+SkinnyKernel select_kernel(int variant, int M, int MT) {
+    switch (variant) {
+        case 0:
+            // the default build exists once per number of H rows it requests at its start
+            if (M <= 2) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 2>;
+            if (M <= 4) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 4>;
+            if (M <= 8) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 8>;
+            if (M <= 10) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 10>;
+            if (M <= 12) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 12>;
+            return skinny_kernel<kMfmaTile, 8, 4, true>;
+        case 1: return skinny_kernel<kMfmaTile, 4, 8, true>;
+        case 2: return skinny_kernel<kMfmaTile, 8, 3, true>;
+        case 3: return skinny_kernel<kMfmaTile, 8, 6, true>;
+        case 4: return MT > 10 ? dot_kernel<8, 2>(MT) : dot_kernel<8, 4>(MT);
+        case 5: return dot_kernel<8, 3>(MT);
+        case 6: return skinny_kernel<kMfmaTile, 8, 4, true, true>;
+        case 7: return skinny_kernel<kMfmaTile, 8, 6, true, true>;
+        case 8: return skinny_kernel<kMfmaTile, 8, 8, true, true>;
+        case 9: return skinny_kernel<kMfmaTile, 9, 4, true, false, true>;
+    }
+    return nullptr;
+}
+
 int lds_bytes(int M, int d, int k, int variant) {
     const int steps = (d / 8 + kLanesAlongD - 1) / kLanesAlongD;
     const Variant &v = kVariants[variant];
@@ -624,6 +639,22 @@ int default_variant(int M, int d, int k, bool vector_alu, bool tiled) {
 }
 
 }  // namespace
+
+// Raises the dynamic LDS limit of every build on the current device (part of the per-device
+// set-up; a launch never changes a function attribute).
+fr_status prepare_skinny_kernels() {
+    for (int variant = 0; variant < kNumVariants; ++variant)
+        for (int M = 1; M <= kSkinnyMaxM; ++M) {
+            const SkinnyKernel kern = select_kernel(variant, M, kVariants[variant].mfma ? kMfmaTile : bucket_for(M));
+            if (!kern) return FR_ERR_HIP;
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    kLdsBudget - kStaticLdsReserve) != hipSuccess) {
+                (void)hipGetLastError();
+                return FR_ERR_HIP;
+            }
+        }
+    return FR_OK;
+}
 
 bool skinny_fits(int M, int d, int k) {
     return M <= kSkinnyMaxM && default_variant(M, d, k, false, false) >= 0;
@@ -701,6 +732,7 @@ fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hip
     a.z_out = p.z_out;
     a.z_ld = p.z_ld;
     a.trace = t ? static_cast<long long *>(t->trace) : nullptr;
+    a.spin_limit = t && t->spin_limit > 0 ? (unsigned)t->spin_limit : 0u;
 
     int grid = a.passes < cus ? a.passes : cus;
     if (t && t->grid > 0) grid = t->grid < a.passes ? t->grid : a.passes;
@@ -728,28 +760,10 @@ fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hip
     }
     const int lds = lds_bytes(p.M, p.d, p.k, variant);
 
-    fr_status st;
-    switch (variant) {
-        case 0:
-            // the default build exists once per number of H rows it requests at its start
-            if (a.M <= 2) st = launch_one<kMfmaTile, 8, 4, true, false, false, 2>(a, grid, lds, s);
-            else if (a.M <= 4) st = launch_one<kMfmaTile, 8, 4, true, false, false, 4>(a, grid, lds, s);
-            else if (a.M <= 8) st = launch_one<kMfmaTile, 8, 4, true, false, false, 8>(a, grid, lds, s);
-            else if (a.M <= 10) st = launch_one<kMfmaTile, 8, 4, true, false, false, 10>(a, grid, lds, s);
-            else if (a.M <= 12) st = launch_one<kMfmaTile, 8, 4, true, false, false, 12>(a, grid, lds, s);
-            else st = launch_one<kMfmaTile, 8, 4, true>(a, grid, lds, s);
-            break;
-        case 1: st = launch_one<kMfmaTile, 4, 8, true>(a, grid, lds, s); break;
-        case 2: st = launch_one<kMfmaTile, 8, 3, true>(a, grid, lds, s); break;
-        case 3: st = launch_one<kMfmaTile, 8, 6, true>(a, grid, lds, s); break;
-        case 4: st = MT > 10 ? launch_dot<8, 2>(MT, a, grid, lds, s) : launch_dot<8, 4>(MT, a, grid, lds, s); break;
-        case 5: st = launch_dot<8, 3>(MT, a, grid, lds, s); break;
-        case 6: st = launch_one<kMfmaTile, 8, 4, true, true>(a, grid, lds, s); break;
-        case 7: st = launch_one<kMfmaTile, 8, 6, true, true>(a, grid, lds, s); break;
-        case 8: st = launch_one<kMfmaTile, 8, 8, true, true>(a, grid, lds, s); break;
-        case 9: st = launch_one<kMfmaTile, 9, 4, true, false, true>(a, grid, lds, s); break;
-        default: return FR_ERR_INVALID_ARG;
-    }
+    const SkinnyKernel kern = select_kernel(variant, a.M, MT);
+    if (!kern) return FR_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kVariants[variant].waves * kWave), lds, s, a);
+    const fr_status st = hip_status(hipGetLastError());
     if (st != FR_OK) return st;
     if (sink == Sink::kPartialsOnly) return launch_merge(p, grid, s);
     return FR_OK;

@@ -11,28 +11,38 @@ import paper_2502_14856_amd as fr
 from paper_2502_14856_amd.binding import Tuning
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "frspec.h")
+HEADERS = [os.path.join(ROOT, "include", n) for n in sorted(os.listdir(os.path.join(ROOT, "include")))
+           if n.endswith(".h")]
 
 INVALID, ALIGN, WORKSPACE, UNSUPPORTED = -1, -2, -3, -5
 
 
 def _declared_symbols():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(fr_[a-z_0-9]+)\s*\(", text)))
+    names = set()
+    for header in HEADERS:
+        text = re.sub(r"/\*.*?\*/", "", open(header).read(), flags=re.S)
+        names |= set(re.findall(r"\b(fr_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
+
+
+def test_product_header_carries_no_measurement_surface():
+    # knobs, traces and calibration kernels are declared in frspec_dev.h only
+    text = open(os.path.join(ROOT, "include", "frspec.h")).read()
+    for word in ("fr_tuning", "fr_calib_", "_tuned", "trace"):
+        assert word not in text, word
 
 
 def test_library_exports_every_declared_symbol():
     L = fr.lib()
     names = _declared_symbols()
     assert {"fr_build_subset", "fr_draft_topk", "fr_full_topk", "fr_workspace_bytes",
-            "fr_workspace_init", "fr_strerror"} <= set(names)
+            "fr_workspace_init", "fr_strerror", "fr_init", "fr_draft_topk_tuned", "fr_calib_read"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
 
 
 def test_strerror_and_version():
-    assert fr.fr_version() >= 100
+    assert fr.fr_version() >= 101
     assert fr.fr_strerror(0) == "ok"
     for code in (-1, -2, -3, -4, -5, -99):
         assert fr.fr_strerror(code)

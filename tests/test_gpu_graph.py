@@ -74,6 +74,7 @@ def test_draft_phase_replayed_from_a_graph_equals_the_eager_calls(fused):
         want.append(snapshot())
     assert not all(np.array_equal(a, b) for a, b in zip(*want))   # the two cases do differ
 
+    fr.fr_init()                       # the per-device set-up never happens inside a capture
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):      # the binding launches on torch's current stream: the capturing one
         phase()
@@ -114,6 +115,7 @@ def test_chunked_kernel_replayed_from_a_graph_equals_the_eager_call(M):
         torch.cuda.synchronize()
         want.append((ids.cpu().numpy().copy(), lp.cpu().numpy().copy()))
     assert not np.array_equal(want[0][0], want[1][0])
+    fr.fr_init()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         fr.fr_draft_topk(H, W_g, idx_g, k, ws, token_ids=ids, logp=lp)

@@ -360,3 +360,51 @@ def test_hidden_states_in_several_blocks(n_blocks, rows, k):
         assert np.array_equal(ids_m.cpu().numpy(), ids_s.cpu().numpy())
         assert np.array_equal(lp_m.cpu().numpy().view(np.uint32), lp_s.cpu().numpy().view(np.uint32))
     del pads
+
+
+@pytest.mark.parametrize("knobs,M,k", [(dict(), 10, 10), (dict(path=2), 40, 10), (dict(), 10, 20),
+                                       (dict(path=2, no_mailbox=1), 24, 10)])
+def test_a_wait_that_runs_out_reports_no_result_and_the_workspace_recovers(knobs, M, k):
+    # The waits inside the single-launch merge are bounded.  Here the bound is forced down to one
+    # poll from the host, so that a merger gives up (every kernel still ends normally): the
+    # subset is one 128-row pass longer than one pass per compute unit, so the first workgroup
+    # streams twice as long as the mergers, which sit at the end of the grid.  Per row either
+    # outcome is accepted: the result of an ordinary call, or "no result" (id INT32_MAX,
+    # logp -inf) together with the sticky word.  After fr_workspace_init the workspace works again.
+    _say("forced time-out", knobs, M, k)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    d, V_sub = 4096, 128 * cus + 128
+    V = V_sub + 100
+    W, H, r = _case(V, d, M, 31)
+    W_g, idx_g = fr.fr_build_subset(to_dev_bf16(W), to_dev_i32(r), V_sub)
+    H_d = to_dev_bf16(H)
+    ws = fr.new_workspace(M, d, V, k)
+    ids_ref, lp_ref = fr.fr_draft_topk(H_d, W_g, idx_g, k, ws)
+    _sync()
+    ids_ref, lp_ref = ids_ref.cpu().numpy(), lp_ref.cpu().numpy()
+    t = Tuning(spin_limit=1, **knobs)
+    gave_up = 0
+    for rep in range(3):
+        ids_g, lp_g = fr.fr_draft_topk(H_d, W_g, idx_g, k, ws, tuning=t)
+        _sync()
+        ids_g, lp_g = ids_g.cpu().numpy(), lp_g.cpu().numpy()
+        timed_out = fr.fr_workspace_check(ws)
+        none = 0
+        for m in range(M):
+            if np.all(ids_g[m] == np.iinfo(np.int32).max):
+                assert np.all(np.isneginf(lp_g[m])), (m, lp_g[m])
+                none += 1
+            else:
+                assert np.array_equal(ids_g[m], ids_ref[m]) and np.array_equal(lp_g[m], lp_ref[m]), m
+        assert (none > 0) == timed_out or (timed_out and none == 0)   # no sentinel row without the word
+        assert none == 0 or timed_out
+        gave_up += none
+        fr.fr_workspace_init(ws)
+        _sync()
+        assert fr.fr_workspace_check(ws) is False
+    _say("  rows that reported no result over 3 calls:", gave_up)
+    assert gave_up > 0
+    ids_g, lp_g = fr.fr_draft_topk(H_d, W_g, idx_g, k, ws)
+    _sync()
+    assert np.array_equal(ids_g.cpu().numpy(), ids_ref) and np.array_equal(lp_g.cpu().numpy(), lp_ref)
+    assert fr.fr_workspace_check(ws) is False
