@@ -43,6 +43,7 @@ typedef void *fr_stream;
 #define FR_ERR_WORKSPACE (-3)   /* workspace smaller than fr_workspace_bytes() */
 #define FR_ERR_HIP (-4)         /* the HIP runtime refused a launch or a query */
 #define FR_ERR_UNSUPPORTED (-5) /* a shape outside what the kernels cover (see fr_draft_topk) */
+#define FR_ERR_SCRATCH (-6)     /* fr_draft_topk_static: more rows of H or a larger k than its scratch holds */
 
 #define FR_K_MAX 64 /* largest k accepted by the top-k calls */
 
@@ -54,7 +55,9 @@ const char *fr_strerror(fr_status status);
  * build, so that afterwards a call only ever launches kernels.  Thread-safe and idempotent.
  * Every entry point that launches performs the same set-up by itself the first time it runs
  * on a device; that first call must not happen while the stream is being captured into a
- * graph.  A program that captures calls fr_init() once per device beforehand (Section 3.1 of
+ * graph.  The set-up also prepares the device's static scratch (see fr_draft_topk_static),
+ * synchronously on the null stream; a repeated fr_init() prepares that scratch again and
+ * must not run while a fr_draft_topk_static call is in flight on the device.  A program that captures calls fr_init() once per device beforehand (Section 3.1 of
  * the paper: everything the drafting loop needs is prepared in advance).
  * Returns FR_ERR_HIP if the runtime refuses a query.
  */
@@ -143,6 +146,26 @@ fr_status fr_draft_topk(const void *H, int64_t M, int64_t d,
                         const void *W_sub, const int32_t *idx_map, int64_t V_sub,
                         int32_t k, int32_t *token_ids, float *logp,
                         void *workspace, size_t workspace_bytes, fr_stream stream);
+
+/*
+ * fr_draft_topk for callers that cannot allocate device memory or carry a workspace around:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * same kernels, the same results bit for bit; the workspace is a static array in device
+ * memory (about 2.2 MiB per device, held until the process ends) instead of an argument.
+ * The call allocates nothing and frees nothing.
+ *   Limits: M <= 16 and k <= 16, else FR_ERR_SCRATCH (nothing is launched).
+ *   The scratch belongs to the DEVICE, not to the call: every call on one device uses the same
+ *   array, so calls that overlap on one device (two streams, two threads) race; order them.
+ *   A completed call leaves the scratch ready for the next one (mailbox records emptied, the
+ *   arrival counters taking turns), whatever the sizes of the two calls.
+ *   The scratch is prepared by the per-device set-up (fr_init, or the first call of any entry
+ *   point on the device: synchronous, not under capture).  Should a call ever be abandoned or
+ *   report "no result" rows (see fr_workspace_check), fr_init() prepares the scratch again.
+ * Arguments and everything else as in fr_draft_topk.
+ */
+fr_status fr_draft_topk_static(const void *H, int64_t M, int64_t d,
+                               const void *W_sub, const int32_t *idx_map, int64_t V_sub,
+                               int32_t k, int32_t *token_ids, float *logp, fr_stream stream);
 
 /*
  * Eq. 2: the same operation over every row of W_full (position == token id).  This is the

@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     fr_draft_step,
     fr_draft_topk,
     fr_draft_topk_multi,
+    fr_draft_topk_static,
     fr_draft_topk_tiled,
     fr_full_topk,
     fr_init,

@@ -76,6 +76,7 @@ def lib():
         L.fr_draft_topk_tiled_tuned.argtypes = [vp, i64, i64, vp, vp, i64, i32, vp, vp, vp, sz, vp,
                                                 ctypes.POINTER(Tuning)]
         L.fr_init.argtypes = []
+        L.fr_draft_topk_static.argtypes = [vp, i64, i64, vp, vp, i64, i32, vp, vp, vp]
         L.fr_draft_step.argtypes = [vp, i64, i64, vp, vp, i64, i32, vp, vp, i32, vp, vp, vp, i64, vp, vp, vp, vp, vp,
                                     vp, sz, vp]
         L.fr_beam_expand.argtypes = [vp, vp, i64, i32, vp, vp, i32, vp, vp, vp, i64, vp, vp, vp, vp]
@@ -84,7 +85,7 @@ def lib():
         L.fr_calib_read.argtypes = [vp, sz, vp, vp]
         for name in ("fr_build_subset", "fr_workspace_init", "fr_workspace_check", "fr_draft_topk", "fr_draft_topk_tuned",
                      "fr_full_topk", "fr_draft_logits", "fr_beam_expand", "fr_tree_select", "fr_draft_step", "fr_draft_topk_multi", "fr_count_tokens", "fr_rank_tokens", "fr_build_subset_tiled",
-                     "fr_draft_topk_tiled", "fr_draft_topk_tiled_tuned", "fr_init", "fr_calib_copy",
+                     "fr_draft_topk_tiled", "fr_draft_topk_tiled_tuned", "fr_init", "fr_draft_topk_static", "fr_calib_copy",
                      "fr_calib_read"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -205,6 +206,23 @@ def fr_draft_topk(H, W_sub, idx_map, k: int, workspace, token_ids=None, logp=Non
                                        _ptr(token_ids), _ptr(logp), _ptr(workspace), ws_bytes,
                                        _stream(stream), ctypes.byref(tuning))
     _check(st, "fr_draft_topk")
+    return token_ids, logp
+
+
+def fr_draft_topk_static(H, W_sub, idx_map, k: int, token_ids, logp, stream=None):
+    """fr_draft_topk on the library's static scratch (M <= 16, k <= 16).  Allocates nothing:
+    the outputs are the caller's."""
+    _bf16_matrix(H, "H")
+    _bf16_matrix(W_sub, "W_sub")
+    M, d = H.shape
+    V_sub = W_sub.shape[0]
+    if W_sub.shape[1] != d:
+        raise ValueError("H and W_sub disagree on d")
+    if tuple(token_ids.shape) != (M, k) or tuple(logp.shape) != (M, k) or token_ids.dtype != torch.int32 \
+            or logp.dtype != torch.float32 or not (token_ids.is_contiguous() and logp.is_contiguous()):
+        raise ValueError("token_ids / logp must be contiguous int32 / float32 [M, k]")
+    _check(lib().fr_draft_topk_static(_ptr(H), M, d, _ptr(W_sub), _ptr(idx_map), V_sub, k, _ptr(token_ids),
+                                      _ptr(logp), _stream(stream)), "fr_draft_topk_static")
     return token_ids, logp
 
 

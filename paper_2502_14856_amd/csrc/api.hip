@@ -7,6 +7,58 @@
 namespace frspec {
 
 namespace {
+constexpr size_t round256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
+
+struct WorkspaceLayout {
+    size_t mail_rec_off, mail_st_off, step_rec_off, ms_off, val_off, id_off, total;
+    // mail_rows: rows of H the result mailbox has records for (the caller's workspace: kMailRows)
+    constexpr WorkspaceLayout(int64_t M, int32_t k, int mail_rows = kMailRows)
+        : mail_rec_off(0), mail_st_off(0), step_rec_off(0), ms_off(0), val_off(0), id_off(0), total(0) {
+        const size_t rows = static_cast<size_t>(M < kMatrixPathMaxM ? M : kMatrixPathMaxM);
+        const size_t slots = static_cast<size_t>(kWorkspaceGridMax) * rows;
+        size_t o = kWorkspaceHeaderBytes;
+        mail_rec_off = o; o += kMailRecBytes / kMailRows * static_cast<size_t>(mail_rows);
+        mail_st_off = o;  o += kMailStBytes / kMailRows * static_cast<size_t>(mail_rows);
+        step_rec_off = o; o += kStepRecBytes;
+        ms_off = o;  o += round256(slots * 2 * sizeof(float));
+        val_off = o; o += round256(slots * static_cast<size_t>(k) * sizeof(float));
+        id_off = o;  o += round256(slots * static_cast<size_t>(k) * sizeof(int));
+        total = o;
+    }
+};
+
+// Scratch of fr_draft_topk_static, the entry point for callers that cannot allocate: one
+// workspace for up to kStaticRows rows of H and k <= kStaticK (header, a 16-row result mailbox,
+// the plain partial arrays; about 2.2 MiB), held by every device the library runs on until the
+// process ends.  The array's name is a host-side stand-in, not a device address: host code
+// uses the address that hipGetSymbolAddress returns for the current device (each device has
+// its own copy), kept in DeviceState::scratch.
+constexpr int kStaticRows = 16, kStaticK = 16;
+constexpr size_t kStaticScratchBytes = WorkspaceLayout(kStaticRows, kStaticK, kStaticRows).total;
+}  // namespace
+}  // namespace frspec
+
+static __device__ __align__(256) unsigned char scratch[frspec::kStaticScratchBytes];
+
+namespace frspec {
+namespace {
+
+// Header zero, every mailbox record empty (all ones): what fr_workspace_init does for a caller's
+// workspace.  Synchronous, on the null stream.
+fr_status prepare_scratch(void *ptr) {
+    constexpr size_t mail = WorkspaceLayout(kStaticRows, kStaticK, kStaticRows).ms_off - kWorkspaceHeaderBytes;
+    fr_status st = launch_fill_u32(static_cast<unsigned *>(ptr), kWorkspaceHeaderBytes / 4, 0u, nullptr);
+    if (st != FR_OK) return st;
+    st = launch_fill_u32(reinterpret_cast<unsigned *>(static_cast<char *>(ptr) + kWorkspaceHeaderBytes), mail / 4,
+                         0xFFFFFFFFu, nullptr);
+    if (st != FR_OK) return st;
+    if (hipStreamSynchronize(nullptr) != hipSuccess) {
+        (void)hipGetLastError();
+        return FR_ERR_HIP;
+    }
+    return FR_OK;
+}
+
 constexpr int kMaxDevices = 64;
 struct DeviceSlot {
     std::atomic<int> ready{0};
@@ -35,6 +87,14 @@ const DeviceState *device_state() {
     if (prepare_skinny_kernels() != FR_OK || prepare_wide_kernels() != FR_OK || prepare_glue_kernels() != FR_OK ||
         prepare_freq_kernels() != FR_OK)
         return nullptr;
+    // this device's copy of the static scratch: its address, then its initial contents
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    if (prepare_scratch(ptr) != FR_OK) return nullptr;
+    slot.state.scratch = ptr;
     slot.ready.store(1, std::memory_order_release);
     return &slot.state;
 }
@@ -47,24 +107,6 @@ int device_cu_count() {
 namespace {
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-inline size_t round256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
-
-struct WorkspaceLayout {
-    size_t mail_rec_off, mail_st_off, step_rec_off, ms_off, val_off, id_off, total;
-    WorkspaceLayout(int64_t M, int32_t k) {
-        const size_t rows = static_cast<size_t>(M < kMatrixPathMaxM ? M : kMatrixPathMaxM);
-        const size_t slots = static_cast<size_t>(kWorkspaceGridMax) * rows;
-        size_t o = kWorkspaceHeaderBytes;
-        mail_rec_off = o; o += kMailRecBytes;
-        mail_st_off = o;  o += kMailStBytes;
-        step_rec_off = o; o += kStepRecBytes;
-        ms_off = o;  o += round256(slots * 2 * sizeof(float));
-        val_off = o; o += round256(slots * static_cast<size_t>(k) * sizeof(float));
-        id_off = o;  o += round256(slots * static_cast<size_t>(k) * sizeof(int));
-        total = o;
-    }
-};
-
 fr_status check_head_args(const void *H, int64_t M, int64_t d, const void *W, int64_t V_rows,
                           int32_t k) {
     if (!H || !W) return FR_ERR_INVALID_ARG;
@@ -81,12 +123,14 @@ fr_status check_head_args(const void *H, int64_t M, int64_t d, const void *W, in
 fr_status head_topk(const void *H, int64_t M, int64_t d, const void *W, const int32_t *idx_map,
                     int64_t V_rows, int32_t k, int32_t *token_ids, float *logp, void *workspace,
                     size_t workspace_bytes, fr_stream stream, const fr_tuning *tuning, bool tiled = false,
-                    const long long *row_delta = nullptr, const StepArgs *step = nullptr) {
+                    const long long *row_delta = nullptr, const StepArgs *step = nullptr,
+                    int mail_rows = kMailRows) {
     fr_status st = check_head_args(H, M, d, W, V_rows, k);
     if (st != FR_OK) return st;
     if (!token_ids || !logp || !workspace) return FR_ERR_INVALID_ARG;
     if (!aligned16(workspace)) return FR_ERR_ALIGNMENT;
-    const WorkspaceLayout wl(M, k);
+    if (M > mail_rows && mail_rows < kMailRows) return FR_ERR_UNSUPPORTED;   // (a short mailbox serves few rows)
+    const WorkspaceLayout wl(M, k, mail_rows);
     if (workspace_bytes < wl.total) return FR_ERR_WORKSPACE;
     if (tuning && (tuning->path < 0 || tuning->path > 3 || tuning->grid < 0 ||
                    tuning->grid > kWorkspaceGridMax || tuning->variant < 0 || tuning->ksplit < 0 ||
@@ -178,13 +222,22 @@ const char *fr_strerror(fr_status status) {
         case FR_ERR_WORKSPACE: return "workspace too small";
         case FR_ERR_HIP: return "HIP runtime error";
         case FR_ERR_UNSUPPORTED: return "shape not supported by the kernels";
+        case FR_ERR_SCRATCH: return "problem larger than the library's static scratch (fr_draft_topk_static: M <= 16, k <= 16)";
     }
     return "unknown status";
 }
 
 int fr_version(void) { return 101; }
 
-fr_status fr_init(void) { return device_state() ? FR_OK : FR_ERR_HIP; }
+fr_status fr_init(void) {
+    int dev = 0;
+    const bool fresh = hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices &&
+                       !g_device[dev].ready.load(std::memory_order_acquire);
+    const DeviceState *st = device_state();
+    if (!st) return FR_ERR_HIP;
+    // a repeated call prepares the device's static scratch afresh (the set-up has just done so)
+    return fresh ? FR_OK : prepare_scratch(st->scratch);
+}
 
 fr_status fr_build_subset(const void *W_full, int64_t V, int64_t d, const int32_t *freq_ranked_ids,
                           int64_t V_sub, void *W_sub, int32_t *idx_map, int32_t *dev_error_flag,
@@ -298,6 +351,18 @@ fr_status fr_draft_topk(const void *H, int64_t M, int64_t d, const void *W_sub,
                         float *logp, void *workspace, size_t workspace_bytes, fr_stream stream) {
     return head_topk(H, M, d, W_sub, idx_map, V_sub, k, token_ids, logp, workspace, workspace_bytes,
                      stream, nullptr);
+}
+
+fr_status fr_draft_topk_static(const void *H, int64_t M, int64_t d, const void *W_sub,
+                               const int32_t *idx_map, int64_t V_sub, int32_t k, int32_t *token_ids,
+                               float *logp, fr_stream stream) {
+    const fr_status chk = check_head_args(H, M, d, W_sub, V_sub, k);
+    if (chk != FR_OK) return chk;
+    if (M > kStaticRows || k > kStaticK) return FR_ERR_SCRATCH;
+    const DeviceState *st = device_state();
+    if (!st || !st->scratch) return FR_ERR_HIP;
+    return head_topk(H, M, d, W_sub, idx_map, V_sub, k, token_ids, logp, st->scratch, kStaticScratchBytes, stream,
+                     nullptr, false, nullptr, nullptr, kStaticRows);
 }
 
 fr_status fr_draft_topk_tuned(const void *H, int64_t M, int64_t d, const void *W_sub,

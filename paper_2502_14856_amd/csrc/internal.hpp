@@ -76,7 +76,8 @@ constexpr int kSkinnyMaxM = 16;          // rows of H the vector-ALU kernel cove
 // the dynamic LDS limit of every kernel build (so that no launch ever changes a function
 // attribute) and is thread-safe.
 struct DeviceState {
-    int cus;   // compute units
+    int cus;         // compute units
+    void *scratch;   // device address of this device's copy of the static scratch (fr_draft_topk_static)
 };
 // State of the current device, after its set-up; nullptr if the set-up failed.
 const DeviceState *device_state();
