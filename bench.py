@@ -29,18 +29,30 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBPS = 8000.0      # MI355X published HBM3E bandwidth
+PEAK_MFMA_BF16_TFLOPS = 2500.0   # MI355X published dense bf16 matrix-core rate
 N_COPIES = 5                # 5 x 256 MiB of W_sub > 256 MB memory-side cache
+TRAFFIC_PROFILE = "profiles/skinny_kernel_llama3_8b_pmc.txt"
 
 
 def _profile_traffic():
     """HBM bytes per launch from the committed rocprofv3 counter summary, if present."""
-    path = os.path.join(ROOT, "profiles", "skinny_kernel_llama3_8b_pmc.txt")
+    path = os.path.join(ROOT, TRAFFIC_PROFILE)
     try:
         text = open(path).read()
     except OSError:
         return None
     m = re.search(r"^hbm_bytes_per_launch:\s*([0-9.eE+]+)", text, flags=re.M)
     return float(m.group(1)) if m else None
+
+
+def _cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.lower().startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def main() -> int:
@@ -107,8 +119,12 @@ def main() -> int:
     ids = torch.empty((M, k), dtype=torch.int32, device="cuda")
     logp = torch.empty((M, k), dtype=torch.float32, device="cuda")
 
+    # one C call per step, its arguments marshalled once per copy of W_sub (a drafting loop
+    # repeats the same call; fr.fr_draft_topk re-checks every tensor on every call)
+    bound = [fr.bind_draft_topk(H, copies[c], idx_map, k, ws, ids, logp) for c in range(N_COPIES)]
+
     def step(i):
-        fr.fr_draft_topk(H, copies[i % N_COPIES], idx_map, k, ws, token_ids=ids, logp=logp)
+        bound[i % N_COPIES]()
 
     # ---- the timed region: exactly K steps between two synchronisations ----
     for i in range(args.warmup):
@@ -153,9 +169,69 @@ def main() -> int:
     ids_f = torch.empty((M, k), dtype=torch.int32, device="cuda")
     lp_f = torch.empty((M, k), dtype=torch.float32, device="cuda")
     t_full = timed(lambda i: fr.fr_full_topk(H, W_full, k, ws, token_ids=ids_f, logp=lp_f),
-                   max(50, args.steps // 4), 10)
+                   max(100, args.steps // 4), 10)
+    # the subset call under the same protocol as the full one (many calls back to back, whatever
+    # --steps is): the two sides of the latency ratio
+    t_sub_steady = timed(step, 400, 20)
     sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
     t_read = timed(lambda i: fr.fr_calib_read(copies[i % N_COPIES], sink), 200, 20)
+
+
+    # ---- every other configuration of the build's measurement table, cold, outside the timed steps
+    def leg(fn, n, warm, rows, d_, M_):
+        t = timed(fn, n, warm)
+        nbytes, flops = rows * d_ * 2, 2.0 * M_ * rows * d_
+        e = {"M": M_, "d": d_, "rows_of_W": rows, "us_per_call_cold": t * 1e6, "calls_per_s": 1.0 / t,
+             "algorithmic_gbps": nbytes / t / 1e9, "hbm_frac": nbytes / t / 1e9 / PEAK_HBM_GBPS}
+        if M_ >= 60:
+            e["tflops"] = flops / t / 1e12
+            e["mfma_bf16_frac"] = flops / t / 1e12 / PEAK_MFMA_BF16_TFLOPS
+        return e
+
+    cfgs = {}
+    ranked_map = ranked_dev            # int32 [V]: any prefix of it is a valid idx_map
+    for vs in (8192, 16384):           # windows of the five copies: 1.25 GiB walked before any repeats
+        wins = [c[j * vs:(j + 1) * vs] for c in copies for j in range(V_sub // vs)]
+        cfgs[f"sweep_V_sub_{vs}"] = leg(lambda i: fr.fr_draft_topk(H, wins[i % len(wins)], ranked_map, k, ws,
+                                                                  token_ids=ids, logp=logp), 400, 20, vs, d, M)
+    cfgs["sweep_V_sub_32768"] = {"M": M, "d": d, "rows_of_W": V_sub, "us_per_call_cold": t_sub_steady * 1e6,
+                                 "calls_per_s": 1.0 / t_sub_steady, "algorithmic_gbps": V_sub * d * 2 / t_sub_steady / 1e9,
+                                 "hbm_frac": V_sub * d * 2 / t_sub_steady / 1e9 / PEAK_HBM_GBPS}
+    wins64 = [W_full[:65536], W_full[V - 65536:]]
+    cfgs["sweep_V_sub_65536"] = leg(lambda i: fr.fr_draft_topk(H, wins64[i % 2], ranked_map, k, ws, token_ids=ids,
+                                                                logp=logp), 200, 10, 65536, d, M)
+    cfgs["sweep_V_sub_128256_full_topk"] = {"M": M, "d": d, "rows_of_W": V, "us_per_call_cold": t_full * 1e6,
+                                            "calls_per_s": 1.0 / t_full, "algorithmic_gbps": V * d * 2 / t_full / 1e9,
+                                            "hbm_frac": V * d * 2 / t_full / 1e9 / PEAK_HBM_GBPS}
+    gen_dev = torch.Generator(device="cuda")
+    gen_dev.manual_seed(20250214)
+    # batched drafting: M = 256 rows of H against the same subset; the full head at M = 64
+    cb = CONFIGS["batched256"]
+    H256 = torch.randn((cb.M, d), device="cuda", generator=gen_dev).to(torch.bfloat16)
+    ws256 = fr.new_workspace(cb.M, d, V, k)
+    ids256 = torch.empty((cb.M, k), dtype=torch.int32, device="cuda")
+    lp256 = torch.empty((cb.M, k), dtype=torch.float32, device="cuda")
+    cfgs["batched_M256"] = leg(lambda i: fr.fr_draft_topk(H256, copies[i % N_COPIES], idx_map, k, ws256,
+                                                          token_ids=ids256, logp=lp256), 100, 10, V_sub, d, cb.M)
+    cfgs["batched_M128"] = leg(lambda i: fr.fr_draft_topk(H256[:128], copies[i % N_COPIES], idx_map, k, ws256,
+                                                          token_ids=ids256[:128], logp=lp256[:128]), 100, 10, V_sub, d, 128)
+    cfgs["full_vocab_M64"] = leg(lambda i: fr.fr_full_topk(H256[:64], W_full, k, ws256, token_ids=ids256[:64],
+                                                           logp=lp256[:64]), 50, 5, V, d, 64)
+    # Qwen-2.5-7B-shaped: d = 3584, V_sub = 32768 of V = 152064, M = 60 (six draft depths batched)
+    cq = CONFIGS["qwen25_7b"]
+    Wq = [(torch.randn((cq.V_sub, cq.d), device="cuda", generator=gen_dev) * 0.02).to(torch.bfloat16)
+          for _ in range(N_COPIES)]
+    Hq = torch.randn((cq.M, cq.d), device="cuda", generator=gen_dev).to(torch.bfloat16)
+    idx_q = torch.randperm(cq.V, device="cuda", generator=gen_dev)[:cq.V_sub].to(torch.int32)
+    ids_q = torch.empty((cq.M, cq.k), dtype=torch.int32, device="cuda")
+    lp_q = torch.empty((cq.M, cq.k), dtype=torch.float32, device="cuda")
+    cfgs["qwen25_7b_M60"] = leg(lambda i: fr.fr_draft_topk(Hq, Wq[i % N_COPIES], idx_q, cq.k, ws256, token_ids=ids_q,
+                                                           logp=lp_q), 200, 20, cq.V_sub, cq.d, cq.M)
+    del Wq
+    cfgs["note"] = ("cold rotation over >= 1 GiB of distinct weights per leg (windows of the five W_sub copies or of "
+                    "W_full); back-to-back calls between two events; hbm_frac = rows*d*2 bytes / time / 8 TB/s; "
+                    "mfma_bf16_frac = 2*M*rows*d flops / time / 2.5 PFLOP/s; the batched and Qwen-shaped legs "
+                    "draw their hidden states (and the Qwen-shaped weights) from a seeded generator on the GPU")
 
     # ---- the glue of a draft phase (Section 2: beam search, depth 6, 60 draft tokens; width 10)
     width, depth, K = 10, 6, 60
@@ -255,7 +331,7 @@ def main() -> int:
         per_call = (time.perf_counter() - t_c) / reps
         match = float(np.mean(ids_o == ids_cold))
         cpu = {"value": 1.0 / per_call, "unit": "calls/s", "cores": oracle.num_threads(),
-               "kind": "oracle",
+               "cpu_model": _cpu_model(), "nproc": os.cpu_count(), "kind": "oracle",
                "sample": f"{reps} full fr_draft_topk-equivalent calls (d={d}, V_sub={V_sub}, M={M}, k={k})",
                "ms_per_call": per_call * 1e3, "gpu_ids_equal_fraction": match}
 
@@ -277,6 +353,9 @@ def main() -> int:
                    "d": d, "V": V, "V_sub": V_sub, "M": M, "k": k},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                      "frac": achieved / PEAK_HBM_GBPS, "traffic": traffic,
+                     "traffic_source": TRAFFIC_PROFILE + " (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE per launch of "
+                                       "this kernel, scaled by a plain read of known size; a committed summary, "
+                                       "not measured in this run)",
                      "kernel": "skinny_kernel<16,8,4,true,false,false,10> (matrix-core build, one launch per call: stream, fold, mailbox merge)",
                      "algorithmic_bytes_per_launch": bytes_per_call},
         "cpu_baseline": cpu,
@@ -290,7 +369,14 @@ def main() -> int:
             "full_topk_us_per_call": t_full * 1e6,
             "full_topk_calls_per_s": 1.0 / t_full,
             "full_topk_gbps": V * d * 2 / t_full / 1e9,
-            "full_over_subset_latency": t_full / t_step,
+            "subset_us_per_call_steady": t_sub_steady * 1e6,
+            "full_over_subset_latency": t_full / t_sub_steady,
+            "full_over_subset_latency_note": "both sides timed the same way: >= 100 calls back to back between two "
+                                             "events, cold rotation (the timed steps of the headline may be few, "
+                                             "and then carry the latency of the first launch after a "
+                                             "synchronisation)",
+            "full_over_headline_step": t_full / t_step,
+            "configs": cfgs,
             "build_subset_us": t_build * 1e6,
             "build_subset_gbps_read_plus_write": 2 * bytes_per_call / t_build / 1e9,
             "beam_expand_us": t_expand * 1e6,

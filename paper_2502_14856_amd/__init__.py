@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     FR_K_MAX,
     FrSpecError,
     Tuning,
+    bind_draft_topk,
     fr_beam_expand,
     fr_build_subset,
     fr_build_subset_tiled,

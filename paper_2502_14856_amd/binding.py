@@ -209,6 +209,35 @@ def fr_draft_topk(H, W_sub, idx_map, k: int, workspace, token_ids=None, logp=Non
     return token_ids, logp
 
 
+def bind_draft_topk(H, W_sub, idx_map, k: int, workspace, token_ids, logp, stream=None):
+    """fr_draft_topk with its arguments checked and marshalled once: returns a function of no
+    arguments that makes the C call on the same buffers each time it is called (a drafting loop
+    repeats one call; the per-call checks of fr_draft_topk cost more host time than the launch).
+    The stream is fixed when the call is bound.  Returns the status-checking callable."""
+    _bf16_matrix(H, "H")
+    _bf16_matrix(W_sub, "W_sub")
+    M, d = H.shape
+    V_sub = W_sub.shape[0]
+    if W_sub.shape[1] != d:
+        raise ValueError("H and W_sub disagree on d")
+    if idx_map is not None and not (idx_map.is_cuda and idx_map.dtype == torch.int32
+                                    and idx_map.is_contiguous() and idx_map.numel() >= V_sub):
+        raise ValueError("idx_map must be a contiguous CUDA int32 tensor with >= V_sub entries")
+    if tuple(token_ids.shape) != (M, k) or tuple(logp.shape) != (M, k) or token_ids.dtype != torch.int32 \
+            or logp.dtype != torch.float32 or not (token_ids.is_contiguous() and logp.is_contiguous()):
+        raise ValueError("token_ids / logp must be contiguous int32 / float32 [M, k]")
+    fn = lib().fr_draft_topk
+    args = (_ptr(H), M, d, _ptr(W_sub), _ptr(idx_map), V_sub, k, _ptr(token_ids), _ptr(logp), _ptr(workspace),
+            workspace.numel() * workspace.element_size(), _stream(stream))
+    keep = (H, W_sub, idx_map, workspace, token_ids, logp)     # the buffers live as long as the bound call
+
+    def call(_keep=keep):
+        st = fn(*args)
+        if st != 0:
+            raise FrSpecError(st, "fr_draft_topk")
+    return call
+
+
 def fr_draft_topk_static(H, W_sub, idx_map, k: int, token_ids, logp, stream=None):
     """fr_draft_topk on the library's static scratch (M <= 16, k <= 16).  Allocates nothing:
     the outputs are the caller's."""
