@@ -35,11 +35,6 @@ typedef struct fr_tuning {
     int32_t spin_limit;  /* > 0: polls after which a wait for other workgroups' results is given up
                             (default: about a second).  Tests set 1 to see the time-out handling
                             with every kernel still ending normally */
-    int32_t two_phase_mode; /* skinny kernel, single pass per workgroup: 0 = two-phase end (default),
-                            1 = one-phase end (fold and merge after the whole pass), 2 = two-phase end
-                            with every workgroup ignoring the thresholds (exercises its fall-backs) */
-    int32_t threshold_slack_milli; /* subtracted from every threshold of the two-phase end, in 1/1000:
-                            more survivors than needed (exercises the paths for many candidates) */
     int32_t reserved;
     void *trace;         /* optional device buffer of 8 * 512 int64: every workgroup of a
                             contraction kernel records 100 MHz timestamps of its phases there */

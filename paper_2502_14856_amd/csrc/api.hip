@@ -34,8 +34,7 @@ struct WorkspaceLayout {
 // uses the address that hipGetSymbolAddress returns for the current device (each device has
 // its own copy), kept in DeviceState::scratch.
 constexpr int kStaticRows = 16, kStaticK = 16;
-constexpr int kStaticMailRows = 48;   // (the skinny kernel's two-phase end uses three mailbox rows per row of H)
-constexpr size_t kStaticScratchBytes = WorkspaceLayout(kStaticRows, kStaticK, kStaticMailRows).total;
+constexpr size_t kStaticScratchBytes = WorkspaceLayout(kStaticRows, kStaticK, kStaticRows).total;
 }  // namespace
 }  // namespace frspec
 
@@ -47,7 +46,7 @@ namespace {
 // Header zero, every mailbox record empty (all ones): what fr_workspace_init does for a caller's
 // workspace.  Synchronous, on the null stream.
 fr_status prepare_scratch(void *ptr) {
-    constexpr size_t mail = WorkspaceLayout(kStaticRows, kStaticK, kStaticMailRows).ms_off - kWorkspaceHeaderBytes;
+    constexpr size_t mail = WorkspaceLayout(kStaticRows, kStaticK, kStaticRows).ms_off - kWorkspaceHeaderBytes;
     fr_status st = launch_fill_u32(static_cast<unsigned *>(ptr), kWorkspaceHeaderBytes / 4, 0u, nullptr);
     if (st != FR_OK) return st;
     st = launch_fill_u32(reinterpret_cast<unsigned *>(static_cast<char *>(ptr) + kWorkspaceHeaderBytes), mail / 4,
@@ -130,12 +129,12 @@ fr_status head_topk(const void *H, int64_t M, int64_t d, const void *W, const in
     if (st != FR_OK) return st;
     if (!token_ids || !logp || !workspace) return FR_ERR_INVALID_ARG;
     if (!aligned16(workspace)) return FR_ERR_ALIGNMENT;
-    if (mail_rows < kMailRows && M > kStaticRows) return FR_ERR_UNSUPPORTED;   // (a short mailbox serves few rows)
+    if (M > mail_rows && mail_rows < kMailRows) return FR_ERR_UNSUPPORTED;   // (a short mailbox serves few rows)
     const WorkspaceLayout wl(M, k, mail_rows);
     if (workspace_bytes < wl.total) return FR_ERR_WORKSPACE;
     if (tuning && (tuning->path < 0 || tuning->path > 3 || tuning->grid < 0 ||
                    tuning->grid > kWorkspaceGridMax || tuning->variant < 0 || tuning->ksplit < 0 ||
-                   tuning->spin_limit < 0 || tuning->two_phase_mode < 0 || tuning->two_phase_mode > 2))
+                   tuning->spin_limit < 0))
         return FR_ERR_INVALID_ARG;
 
     char *ws = static_cast<char *>(workspace);
@@ -149,7 +148,6 @@ fr_status head_topk(const void *H, int64_t M, int64_t d, const void *W, const in
     p.d = static_cast<int>(d);
     p.V_rows = static_cast<int>(V_rows);
     p.k = k;
-    p.mail_rows = mail_rows;
     p.ws.ticket = reinterpret_cast<unsigned *>(ws);
     p.ws.mail_rec = reinterpret_cast<unsigned long long *>(ws + wl.mail_rec_off);
     p.ws.mail_st = reinterpret_cast<unsigned long long *>(ws + wl.mail_st_off);
@@ -364,7 +362,7 @@ fr_status fr_draft_topk_static(const void *H, int64_t M, int64_t d, const void *
     const DeviceState *st = device_state();
     if (!st || !st->scratch) return FR_ERR_HIP;
     return head_topk(H, M, d, W_sub, idx_map, V_sub, k, token_ids, logp, st->scratch, kStaticScratchBytes, stream,
-                     nullptr, false, nullptr, nullptr, kStaticMailRows);
+                     nullptr, false, nullptr, nullptr, kStaticRows);
 }
 
 fr_status fr_draft_topk_tuned(const void *H, int64_t M, int64_t d, const void *W_sub,

@@ -318,9 +318,7 @@ __device__ __forceinline__ void lds_words(const T *p, T (&out)[C]) {
 // Where a fold puts its results: the workgroup's running state in LDS, or, on the
 // workgroup's last pass, straight into the workspace (slot g of the partials, or of the
 // mailbox).
-// (the two-phase end of the skinny kernel: kMailboxP1 = list records out, statistics kept in LDS;
-// kMailboxP2 = list records out, at mailbox row mail_row0 + m, statistics dropped)
-enum class FoldTo : int { kLds = 0, kPartials = 1, kMailbox = 2, kMailboxP1 = 3, kMailboxP2 = 4 };
+enum class FoldTo : int { kLds = 0, kPartials = 1, kMailbox = 2 };
 struct FoldSink {
     FoldTo to;
     Partials part;
@@ -329,10 +327,9 @@ struct FoldSink {
     float *run_ms;
     float *run_val;
     int *run_id;
-    int mail_row0 = 0;
     __device__ __forceinline__ void entry(int m, int k, int slot, float v, int id) const {
-        if (to == FoldTo::kMailbox || to == FoldTo::kMailboxP1 || to == FoldTo::kMailboxP2) {
-            publish(mail.rec + mail_rec_index(mail_row0 + m, slot, g), mail_pack(v, (unsigned)id));
+        if (to == FoldTo::kMailbox) {
+            publish(mail.rec + mail_rec_index(m, slot, g), mail_pack(v, (unsigned)id));
         } else if (to == FoldTo::kPartials) {
             publish(part.val + part_index(m * k + slot, g), v);
             publish(part.id + part_index(m * k + slot, g), id);
@@ -347,7 +344,7 @@ struct FoldSink {
         } else if (to == FoldTo::kPartials) {
             publish(part.ms + part_index(m * 2, g), mx);
             publish(part.ms + part_index(m * 2 + 1, g), S);
-        } else if (to != FoldTo::kMailboxP2) {
+        } else {
             run_ms[2 * m] = mx;
             run_ms[2 * m + 1] = S;
         }

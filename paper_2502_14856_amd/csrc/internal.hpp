@@ -53,7 +53,6 @@ struct HeadProblem {
     bool tiled;
     const int *idx_map;   // nullable
     int M, d, V_rows, k;
-    int mail_rows;        // rows of H the workspace's result mailbox has records for
     int *token_ids;       // [M, k]
     float *logp;          // [M, k]
     float *z_out;         // [M, V_rows] (Sink::kLogits only)

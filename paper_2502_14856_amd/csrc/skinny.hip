@@ -24,7 +24,6 @@
 // (KS > 1) so that every compute unit still has enough loads in flight.
 #include "epilogue.hpp"
 #include "internal.hpp"
-#include "two_phase.hpp"
 
 namespace frspec {
 namespace {
@@ -64,9 +63,6 @@ struct SkinnyArgs {
     int passes;           // ceil(V_rows / rows per pass)
     int sink;
     unsigned spin_limit;  // polls after which a wait for other workgroups is given up (0: the default)
-    int two_phase;        // 1: the two-phase end (single pass per workgroup; see two_phase.hpp), 2: the same
-                          // with every workgroup ignoring the thresholds (exercises the fall-backs)
-    float t_slack;        // subtracted from every threshold (tests: more survivors than needed)
     Partials part;
     Mailbox mail;
     StepArgs step;
@@ -101,72 +97,6 @@ struct SkinnyLds {
 };
 
 /*
- * The two-phase end of the default build's single-pass case (see two_phase.hpp), called by all
- * eight wavefronts once their tile's logits are in LDS.  `ap` points at the kernel's argument
- * block; a logit slice is 16 columns wide.
- */
-__device__ __noinline__ void two_phase_end(const SkinnyArgs *ap, int n_valid, float *z_lds, int *ids_lds,
-                                           float *run_ms, float *run_val, int *run_id, SelectScratch *sel,
-                                           TwoPhaseLds *tp) {
-    const SkinnyArgs &a = *ap;
-    const int tid = (int)threadIdx.x, lane = tid & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
-    const int G = (int)gridDim.x, b = (int)blockIdx.x;
-    const int KS = a.KS, ZR = (8 / KS) * kTileRows, slice = 16 * ZR;
-    auto stamp = [&](int slot, bool who) {
-        if (a.trace && who) a.trace[b * 8 + slot] = (long long)__builtin_amdgcn_s_memrealtime();
-    };
-    // the merging workgroups: every 8th from the end of the grid, one row of H each (as in the
-    // one-phase path)
-    const int R = merger_count(G, a.M);
-    const int spread = 8 * (R - 1) < G ? 8 : 1;
-    const int top = (G - 1) / spread * spread;
-    const int mr = (b > top || b % spread != 0 || (top - b) / spread >= R) ? -1 : (top - b) / spread;
-    const unsigned spin = a.spin_limit ? a.spin_limit : kMailSpinLimit;
-    unsigned long long *tbox = reinterpret_cast<unsigned long long *>(a.ticket + kTboxWord);
-    const Partials part = a.part;
-    const Mailbox mail = a.mail;
-    unsigned epoch = 0u;
-    if (wave < 4) {
-        // this call's number validates the threshold records (asked for while waiting for the others)
-        epoch = (unsigned)__builtin_amdgcn_readfirstlane((int)observe(a.ticket + kEpochWord)) + 1u;
-        group_sync(&tp->early_arrived, 4u);   // the early half of the logits is in LDS
-        stamp(2, tid == 0);
-        auto row_of = [&](int m) {
-            return FoldRow{z_lds + m * ZR, run_ms + 2 * m, run_val + m * a.k, run_id + m * a.k};
-        };
-        const FoldSink out1{FoldTo::kMailboxP1, part, mail, b, run_ms, run_val, run_id, 0};
-        fold_pass<64, false, false, false>(z_lds, ZR, KS, slice, ids_lds, min(n_valid, ZR >> 1), a.k, 0, a.M, wave, 4,
-                                           row_of, out1, sel + wave);
-        if (mr >= 0) merge_phase1(mail, a.ticket + 1, G, mr, a.k, tp, spin, epoch, tbox, wave);
-        if (wave == 0) {
-            stamp(6, lane == 0);
-            collect_thresholds(tbox, a.M, epoch, tp);
-        }
-    } else {
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        if (lane == 0) __hip_atomic_fetch_add(&tp->late_done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        stamp(7, wave == 4 && lane == 0);
-    }
-    __syncthreads();
-    fold_final_pair(z_lds, ZR, KS, slice, ids_lds, n_valid, a.k, wave, wave + 8, a.M, part, mail, b, run_ms, run_val,
-                    run_id, tp, a.two_phase == 1, a.t_slack, sel + wave);
-    stamp(3, tid == 0);
-    if (mr < 0) return;
-    stamp(4, tid == 0);
-    merge_final(mail, part, a.ticket + 1, G, mr, a.M, a.k, a.token_ids, a.logp, tp, sel, a.step.rec, spin);
-    if (mr == 0 && wave == 0) {
-        if (a.step.rec)
-            expand_step_fused(a.step, a.M, a.k, reinterpret_cast<unsigned long long *>(sel), a.ticket + 1, spin);
-        // the next call's number; the thresholds of this one are stale from now on
-        if (lane == 0) publish(a.ticket + kEpochWord, epoch == 0xFFFFFFFFu ? 0u : epoch);
-        if (epoch == 0xFFFFFFFFu && lane < kStepRows) publish(tbox + lane, 0ull);
-    }
-    __syncthreads();
-    stamp(5, tid == 0);
-}
-
-/*
  * SKEW build (single pass per workgroup, row-major W, matrix cores): the eight compute dies do
  * not stream at the same rate (the odd-numbered ones are consistently ~9% slower), workgroups
  * are dealt to the dies in turn, and the kernel ends with the slowest die.  So every odd
@@ -187,20 +117,19 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     // memory (the block is new with every launch).  One load per line, all issued at once,
     // brings the lines into the scalar cache in a single trip; the rounds then hit.
     {
-        static_assert(sizeof(SkinnyArgs) <= 7 * 64, "one load per 64-byte line of the argument block");
+        static_assert(sizeof(SkinnyArgs) <= 6 * 64, "one load per 64-byte line of the argument block");
         typedef const __attribute__((address_space(4))) unsigned *ConstWords;
         ConstWords ka = (ConstWords)__builtin_amdgcn_kernarg_segment_ptr();
-        unsigned w0, w1, w2, w3, w4, w5, w6;
+        unsigned w0, w1, w2, w3, w4, w5;
         asm volatile(
-            "s_load_dword %0, %7, 0x0\n\t"
-            "s_load_dword %1, %7, 0x40\n\t"
-            "s_load_dword %2, %7, 0x80\n\t"
-            "s_load_dword %3, %7, 0xc0\n\t"
-            "s_load_dword %4, %7, 0x100\n\t"
-            "s_load_dword %5, %7, 0x140\n\t"
-            "s_load_dword %6, %7, 0x180\n\t"
+            "s_load_dword %0, %6, 0x0\n\t"
+            "s_load_dword %1, %6, 0x40\n\t"
+            "s_load_dword %2, %6, 0x80\n\t"
+            "s_load_dword %3, %6, 0xc0\n\t"
+            "s_load_dword %4, %6, 0x100\n\t"
+            "s_load_dword %5, %6, 0x140\n\t"
             "s_waitcnt lgkmcnt(0)"
-            : "=&s"(w0), "=&s"(w1), "=&s"(w2), "=&s"(w3), "=&s"(w4), "=&s"(w5), "=&s"(w6)
+            : "=&s"(w0), "=&s"(w1), "=&s"(w2), "=&s"(w3), "=&s"(w4), "=&s"(w5)
             : "s"(ka)
             : "memory");
     }
@@ -231,9 +160,6 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     __shared__ int s_slot;
     __shared__ SelectScratch s_select[WAVES];
     __shared__ MergeScratch s_merge;
-    __shared__ TwoPhaseLds s_tp;
-    // the two-phase end exists in the default build only (eight wavefronts, matrix cores, row-major W)
-    constexpr bool kTwoPhaseBuild = MFMA && !TILED && !SKEW && WAVES == 8;
     const Partials part = a.part;   // a local copy keeps the argument block itself in registers
 
     constexpr int ZR_MAX = FOLD_WAVES * kTileRows;   // local rows that the fold's lanes cover
@@ -370,19 +296,6 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
             }
     }
     // (the running state needs no reset: a workgroup's first pass overwrites all of it)
-    if constexpr (kTwoPhaseBuild) {
-        if (tid < kWave) s_tp.key[tid] = 0ull;
-        if (tid == 0) {
-            s_tp.T_mask = 0u;
-            s_tp.early_arrived = 0u;
-            s_tp.late_done = 0u;
-            s_tp.p1_count = 0u;
-            s_tp.p1_failed = 0u;
-            s_tp.n_cand = 0u;
-            s_tp.n_flag = 0u;
-            s_tp.timed_out = 0u;
-        }
-    }
     __syncthreads();
     stamp(1);
 
@@ -538,15 +451,6 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
 #pragma unroll
                     for (int r = 0; r < kRowsPerLane; ++r)
                         z_lds[(ks * MT + m) * ZR + rl + r] = acc[r][m];
-            }
-        }
-        if constexpr (kTwoPhaseBuild) {
-            if (a.two_phase) {
-                // The two-phase end of the workgroup's only pass, out of line and fed from the
-                // argument block itself: nothing of it is live across the stream above.
-                two_phase_end((const SkinnyArgs *)__builtin_amdgcn_kernarg_segment_ptr(), n_valid, z_lds, ids_lds,
-                              run_ms, run_val, run_id, s_select, &s_tp);
-                return;
             }
         }
         __syncthreads();
@@ -855,17 +759,6 @@ fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hip
         }
     }
     const int lds = lds_bytes(p.M, p.d, p.k, variant);
-
-    // The two-phase end: default build, results through the mailbox, every workgroup exactly one
-    // pass, at least two tiles per pass (an early and a late half), one merging workgroup per
-    // row of H, and a mailbox with the rows it uses.
-    const int tp_mode = t ? t->two_phase_mode : 0;
-    a.two_phase = (variant == 0 && sink == Sink::kFusedTopk && p.k <= kSmallKMax && grid <= 4 * kWave &&
-                   a.passes == grid && KS <= 4 && p.M <= grid && p.M <= kStepRows && p.mail_rows >= kTwoPhaseMailRows &&
-                   tp_mode != 1)
-                      ? (tp_mode == 2 ? 2 : 1)
-                      : 0;
-    a.t_slack = t ? 1e-3f * (float)t->threshold_slack_milli : 0.0f;
 
     const SkinnyKernel kern = select_kernel(variant, a.M, MT);
     if (!kern) return FR_ERR_INVALID_ARG;
