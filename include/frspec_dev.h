@@ -20,7 +20,8 @@ extern "C" {
 typedef struct fr_tuning {
     int32_t path;        /* 3 = skinny kernel (M <= 16), products on the matrix cores (default),
                             1 = skinny kernel, products on the vector ALUs (bf16 dot2),
-                            2 = chunked matrix-core kernel (any M) */
+                            2 = matrix-core kernels for any M: the chunked kernel up to 64 rows of H,
+                            the block kernel beyond (where it serves the shape) */
     int32_t two_launch;  /* 1 = merge the per-workgroup partials in a second launch instead
                             of inside the same launch */
     int32_t variant;     /* skinny kernel build variant, 1-based (waves x pipeline depth x unit) */
@@ -35,7 +36,8 @@ typedef struct fr_tuning {
     int32_t spin_limit;  /* > 0: polls after which a wait for other workgroups' results is given up
                             (default: about a second).  Tests set 1 to see the time-out handling
                             with every kernel still ending normally */
-    int32_t reserved;
+    int32_t chunked_only; /* 1 = more than 64 rows of H also go to the chunked kernel, in slabs of up to
+                            128 rows with one pass over W per slab (the path before the block kernel) */
     void *trace;         /* optional device buffer of 8 * 512 int64: every workgroup of a
                             contraction kernel records 100 MHz timestamps of its phases there */
 } fr_tuning;

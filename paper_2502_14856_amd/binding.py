@@ -30,7 +30,7 @@ class Tuning(ctypes.Structure):
                 ("variant", ctypes.c_int32), ("ksplit", ctypes.c_int32),
                 ("grid", ctypes.c_int32), ("stream_only", ctypes.c_int32),
                 ("skew", ctypes.c_int32), ("no_mailbox", ctypes.c_int32),
-                ("spin_limit", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("spin_limit", ctypes.c_int32), ("chunked_only", ctypes.c_int32),
                 ("trace", ctypes.c_void_p)]
 
 

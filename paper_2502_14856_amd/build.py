@@ -18,7 +18,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libfrspec.so")
 
-SOURCES = ["api.hip", "skinny.hip", "mfma.hip", "merge.hip", "gather.hip", "glue.hip", "freq.hip", "calib.hip"]
+SOURCES = ["api.hip", "skinny.hip", "mfma.hip", "gemm.hip", "merge.hip", "gather.hip", "glue.hip", "freq.hip", "calib.hip"]
 
 # Packed fp32 VALU instructions are switched off for every device translation unit.
 HIP_FLAGS = [

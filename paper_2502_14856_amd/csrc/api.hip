@@ -84,7 +84,7 @@ const DeviceState *device_state() {
         return nullptr;
     }
     slot.state.cus = n;
-    if (prepare_skinny_kernels() != FR_OK || prepare_wide_kernels() != FR_OK || prepare_glue_kernels() != FR_OK ||
+    if (prepare_skinny_kernels() != FR_OK || prepare_wide_kernels() != FR_OK || prepare_block_kernels() != FR_OK || prepare_glue_kernels() != FR_OK ||
         prepare_freq_kernels() != FR_OK)
         return nullptr;
     // this device's copy of the static scratch: its address, then its initial contents
@@ -186,12 +186,18 @@ fr_status head_topk(const void *H, int64_t M, int64_t d, const void *W, const in
         return launch_skinny(p, stream_only ? Sink::kStreamOnly : two_launch ? Sink::kPartialsOnly : Sink::kFusedTopk, tuning, s);
     }
 
-    // matrix-core path: slabs of H rows, each a full pass over W (a build costs the same for
-    // any number of rows up to its size, so full slabs first beat equal shares)
+    // matrix-core path: slabs of H rows, each a full pass over W.  More than 64 rows go to the
+    // block kernel, up to 256 at a time, where it serves the shape; otherwise, and for what is
+    // left, the chunked kernel takes slabs of up to 128 (a build costs the same for any number
+    // of rows up to its size, so full slabs first beat equal shares).
     const int slab = mfma_max_rows(k);
     if (slab <= 0) return FR_ERR_UNSUPPORTED;
-    for (int64_t m0 = 0; m0 < M; m0 += slab) {
-        const int rows = static_cast<int>(M - m0 < slab ? M - m0 : slab);
+    const bool chunked_only = tuning && tuning->chunked_only;
+    for (int64_t m0 = 0; m0 < M;) {
+        const int64_t left = M - m0;
+        const int block_rows = static_cast<int>(left < kBlockMaxM ? left : kBlockMaxM);
+        const bool block = !chunked_only && block_kernel_serves(block_rows, (int)d, k);
+        const int rows = block ? block_rows : static_cast<int>(left < slab ? left : slab);
         p.H = static_cast<const char *>(H) + static_cast<size_t>(m0) * d * 2;
         p.M = rows;
         p.token_ids = token_ids + m0 * k;
@@ -201,8 +207,9 @@ fr_status head_topk(const void *H, int64_t M, int64_t d, const void *W, const in
         const bool mail_ok = k <= kMailK && rows <= kMailRows && !(tuning && tuning->no_mailbox);
         const Sink sink = stream_only ? Sink::kStreamOnly
                           : (two_launch || (rows > 32 && !mail_ok)) ? Sink::kPartialsOnly : Sink::kFusedTopk;
-        st = launch_mfma(p, sink, tuning, s, nullptr);
+        st = block ? launch_block(p, sink, tuning, s) : launch_mfma(p, sink, tuning, s, nullptr);
         if (st != FR_OK) return st;
+        m0 += rows;
     }
     return FR_OK;
 }
@@ -399,13 +406,17 @@ fr_status fr_draft_logits(const void *H, int64_t M, int64_t d, const void *W, in
         return launch_skinny(p, Sink::kLogits, nullptr, s);
     }
     const int slab = mfma_max_rows(1);
-    for (int64_t m0 = 0; m0 < M; m0 += slab) {
-        const int rows = static_cast<int>(M - m0 < slab ? M - m0 : slab);
+    for (int64_t m0 = 0; m0 < M;) {
+        const int64_t left = M - m0;
+        const int block_rows = static_cast<int>(left < kBlockMaxM ? left : kBlockMaxM);
+        const bool block = block_kernel_serves(block_rows, (int)d, 1);
+        const int rows = block ? block_rows : static_cast<int>(left < slab ? left : slab);
         p.H = static_cast<const char *>(H) + static_cast<size_t>(m0) * d * 2;
         p.M = rows;
         p.z_out = z_out + static_cast<size_t>(m0) * V_rows;
-        st = launch_mfma(p, Sink::kLogits, nullptr, s, nullptr);
+        st = block ? launch_block(p, Sink::kLogits, nullptr, s) : launch_mfma(p, Sink::kLogits, nullptr, s, nullptr);
         if (st != FR_OK) return st;
+        m0 += rows;
     }
     return FR_OK;
 }

@@ -86,6 +86,7 @@ int device_cu_count();
 // The parts of the set-up that live with their kernels.
 fr_status prepare_skinny_kernels();
 fr_status prepare_wide_kernels();
+fr_status prepare_block_kernels();
 fr_status prepare_glue_kernels();
 fr_status prepare_freq_kernels();
 
@@ -102,6 +103,12 @@ fr_status launch_mfma(const HeadProblem &p, Sink sink, const fr_tuning *t, hipSt
                       int *grid_used);
 // Largest slab of H rows (multiple of 16, <= 128) whose per-row state fits LDS for this k.
 int mfma_max_rows(int k);
+
+// gemm.hip: register-blocked matrix-core kernel for kBlockMinM <= M <= kBlockMaxM rows of H per
+// launch (d a multiple of 128, k <= 16); W is read once for all of them.
+constexpr int kBlockMinM = 65, kBlockMaxM = 256;
+bool block_kernel_serves(int M, int d, int k);
+fr_status launch_block(const HeadProblem &p, Sink sink, const fr_tuning *t, hipStream_t s);
 
 // merge.hip: merges G partial slots per row of H into the outputs.
 fr_status launch_merge(const HeadProblem &p, int G, hipStream_t s);

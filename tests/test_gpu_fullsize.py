@@ -14,6 +14,7 @@ import torch
 
 import oracle
 import paper_2502_14856_amd as fr
+from paper_2502_14856_amd.binding import Tuning
 from parity_utils import TIGHT_TOL, bits_of, check_topk_against_oracle, to_dev_bf16, to_dev_i32
 from synth import CONFIGS, SWEEP_V_SUB, make_hidden, make_weights, zipf_ranking
 
@@ -108,7 +109,7 @@ def _report(what, rep):
     _say(f"  {what}: rows identical to the oracle {float(rep):.3f}, max |logp - oracle| {rep.logp_err:.2e}")
 
 
-def _all_rows_check(cfg_name, full, M=None):
+def _all_rows_check(cfg_name, full, M=None, tuning=None):
     """Every row of H of a batched configuration against the oracle (the oracle takes about
     5 ms per row at these shapes), log-probabilities inside the tight band."""
     c = CONFIGS[cfg_name]
@@ -120,13 +121,14 @@ def _all_rows_check(cfg_name, full, M=None):
     W_d, H_d = to_dev_bf16(W), to_dev_bf16(H)
     ws = fr.new_workspace(M, c.d, c.V, c.k)
     if full:
+        assert tuning is None
         ids_g, lp_g = fr.fr_full_topk(H_d, W_d, c.k, ws)
         torch.cuda.synchronize()
         ids_o, lp_o, z_o = oracle.full_topk(H, W, c.k, want_logits=True)
         idx_o = None
     else:
         W_g, idx_g = fr.fr_build_subset(W_d, to_dev_i32(r), c.V_sub)
-        ids_g, lp_g = fr.fr_draft_topk(H_d, W_g, idx_g, c.k, ws)
+        ids_g, lp_g = fr.fr_draft_topk(H_d, W_g, idx_g, c.k, ws, tuning=tuning)
         torch.cuda.synchronize()
         W_o, idx_o = oracle.build_subset(W, r, c.V_sub)
         assert np.array_equal(idx_g.cpu().numpy(), idx_o)
@@ -142,8 +144,19 @@ def test_qwen25_7b_shape_all_rows():
 
 
 def test_batched256_shape_all_rows():
-    # (rows 127 / 128 sit on either side of the boundary between the two slabs of H)
+    # one launch of the block kernel (256 rows of H against one pass over W_sub) and a merge launch
     _all_rows_check("batched256", full=False)
+
+
+def test_batched256_shape_all_rows_chunked_kernel():
+    # the same through the chunked kernel: two slabs of 128 rows of H (rows 127 / 128 sit on either
+    # side of the boundary), W_sub read once per slab
+    _all_rows_check("batched256", full=False, tuning=Tuning(chunked_only=1))
+
+
+def test_full_vocab_m256_all_rows():
+    # the uncompressed head at 256 rows of H: every workgroup of the block kernel takes four passes
+    _all_rows_check("batched256", full=True)
 
 
 def test_full_vocab_m64_all_rows():
@@ -165,19 +178,22 @@ def batched():
     return c, H, W_g, idx_g, W_o, idx_o
 
 
-@pytest.mark.parametrize("M", [14, 30, 48, 64, 96, 128])
-def test_every_build_of_the_chunked_kernel_at_full_size(batched, M):
+@pytest.mark.parametrize("M,block", [(14, False), (30, False), (48, False), (64, False), (96, False), (128, False),
+                                     (65, True), (96, True), (128, True), (130, True), (192, True), (250, True)])
+def test_every_build_of_the_matrix_core_kernels_at_full_size(batched, M, block):
     # the batched configuration's weights and ranking with the first M of its 256 rows of H: one
     # M per build of the chunked kernel (16, 32, 48, 64, 96 and 128 rows; the 8-wavefront skinny
-    # kernel stops at 12 rows for d = 4096); every row against the oracle
+    # kernel stops at 12 rows for d = 4096) and of the block kernel (128, 192 and 256 rows, which
+    # takes over beyond 64 rows by default); every row against the oracle
     c, H, W_g, idx_g, W_o, idx_o = batched
     ws = fr.new_workspace(M, c.d, c.V_sub, c.k)
-    ids_g, lp_g = fr.fr_draft_topk(to_dev_bf16(H[:M]), W_g, idx_g, c.k, ws)
+    ids_g, lp_g = fr.fr_draft_topk(to_dev_bf16(H[:M]), W_g, idx_g, c.k, ws,
+                                   tuning=None if block else Tuning(chunked_only=1))
     torch.cuda.synchronize()
     ids_o, lp_o, z_o = oracle.draft_topk(H[:M], W_o, idx_o, c.k, want_logits=True)
     rep = check_topk_against_oracle(ids_g.cpu().numpy(), lp_g.cpu().numpy(), z_o, idx_o, ids_o, lp_o,
                                     logp_tight=TIGHT_TOL)
-    _report(f"chunked kernel M={M}", rep)
+    _report(f"{'block' if block else 'chunked'} kernel M={M}", rep)
 
 
 @pytest.mark.parametrize("M,k", [(1, 10), (1, 1), (10, 17), (10, 64), (1, 64), (60, 17), (16, 16)])

@@ -174,6 +174,51 @@ def test_draft_topk_matrix_core(M, d, V, V_sub, k):
     _say("  rows identical to the oracle:", frac)
 
 
+# The block kernel takes 65 to 256 rows of H per launch when d is a multiple of 128 and k <= 16:
+# its three builds (up to 128, 192 and 256 rows), vocabulary sizes that are no multiple of its
+# 128-row pass, more rows than one launch holds, few workgroups (several passes per workgroup:
+# the running lists compete), both merge routes, and the same calls through the chunked kernel.
+_BLOCK_CASES = [
+    (65, 128, 3000, 300, 10, {}), (128, 256, 5000, 2500, 16, {}), (129, 128, 3000, 1500, 1, {}),
+    (192, 384, 4000, 1000, 10, {}), (200, 1024, 4000, 2048, 7, {}), (256, 256, 3000, 1500, 10, {}),
+    (300, 128, 2000, 900, 5, {}), (600, 128, 1500, 640, 3, {}), (100, 256, 9000, 4099, 10, dict(grid=3)),
+    (256, 128, 9000, 9000, 16, dict(grid=5)), (96, 512, 2000, 1000, 12, dict(two_launch=1)),
+    (120, 256, 3000, 129, 10, dict(no_mailbox=1)), (70, 2048, 1000, 127, 4, {}), (256, 4096, 700, 700, 10, {})]
+
+
+@pytest.mark.parametrize("M,d,V,V_sub,k,knobs", _BLOCK_CASES)
+def test_draft_topk_block_kernel(M, d, V, V_sub, k, knobs):
+    _say("draft block kernel", M, d, V, V_sub, k, knobs)
+    W, H, r = _case(V, d, M, 60)
+    t = Tuning(path=2, **knobs)
+    frac, ids_b, lp_b = _run_draft(W, H, r, V_sub, k, tuning=t)
+    _say("  rows identical to the oracle (block kernel):", frac)
+    t = Tuning(path=2, chunked_only=1, **knobs)
+    frac, ids_c, lp_c = _run_draft(W, H, r, V_sub, k, tuning=t)
+    _say("  rows identical to the oracle (chunked kernel, slabs):", frac)
+
+
+@pytest.mark.parametrize("M,k", [(80, 12), (256, 12), (130, 16)])
+def test_draft_topk_block_kernel_exact_inputs_identical_with_ties(M, k):
+    # integer-valued inputs, logits full of ties: the ids must match the oracle with no exemption
+    # (the general fold and merge run where more than 32 candidates of a row tie)
+    _say("draft block kernel, exact + ties", M, k)
+    W_bits, H_bits, _, _ = make_exact_case(V=3000, d=128, M=M, seed=300 + M, w_levels=1, h_levels=1)
+    r = np.random.default_rng(12).permutation(3000).astype(np.int32)
+    frac, _, _ = _run_draft(W_bits, H_bits, r, 1500, k, exact=True)
+    assert frac == 1.0
+
+
+@pytest.mark.parametrize("M,d,V", [(65, 128, 129), (128, 4096, 300), (192, 256, 1000), (256, 512, 513), (600, 128, 260)])
+def test_logits_block_kernel_exact_inputs_bit_exact(M, d, V):
+    _say("logits block kernel, exact", M, d, V)
+    W_bits, H_bits, W_int, H_int = make_exact_case(V=V, d=d, M=M, seed=M + V)
+    exact = (H_int @ W_int.T).astype(np.float32)
+    z_g = fr.fr_draft_logits(to_dev_bf16(H_bits), to_dev_bf16(W_bits))
+    _sync()
+    assert np.array_equal(z_g.cpu().numpy(), exact)
+
+
 @pytest.mark.parametrize("M", [4, 10, 48])
 def test_draft_topk_exact_inputs_identical_with_ties(M):
     # Integer-valued inputs: logits are exact on both sides and full of ties, so the
