@@ -64,6 +64,9 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--only-steps", action="store_true",
                     help="run nothing but warm-up and the timed steps (clean kernel profiles)")
+    ap.add_argument("--only-batched", type=int, default=0, metavar="M",
+                    help="run nothing but the batched leg with M rows of H (matrix-core kernels: clean "
+                         "profiles), --steps calls by default routing, then as many through the chunked kernel")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)",
@@ -118,6 +121,27 @@ def main() -> int:
     ws = fr.new_workspace(M, d, V, k)
     ids = torch.empty((M, k), dtype=torch.int32, device="cuda")
     logp = torch.empty((M, k), dtype=torch.float32, device="cuda")
+
+    if args.only_batched > 0:
+        from paper_2502_14856_amd.binding import Tuning
+        Mb = args.only_batched
+        gen_b = torch.Generator(device="cuda")
+        gen_b.manual_seed(20250214)
+        Hb = torch.randn((Mb, d), device="cuda", generator=gen_b).to(torch.bfloat16)
+        wsb = fr.new_workspace(Mb, d, V, k)
+        idsb = torch.empty((Mb, k), dtype=torch.int32, device="cuda")
+        lpb = torch.empty((Mb, k), dtype=torch.float32, device="cuda")
+        out = {"only_batched": Mb, "steps": args.steps, "warmup": args.warmup}
+        for tag, tun in (("default", None), ("chunked_kernel", Tuning(chunked_only=1))):
+            t = timed(lambda i: fr.fr_draft_topk(Hb, copies[i % N_COPIES], idx_map, k, wsb, token_ids=idsb, logp=lpb,
+                                                 tuning=tun), args.steps, args.warmup)
+            out[f"us_per_call_{tag}"] = t * 1e6
+        sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
+        for i in range(10):     # the kernel of known traffic that calibrates the byte counters
+            fr.fr_calib_read(copies[i % N_COPIES], sink)
+        torch.cuda.synchronize()
+        print(json.dumps(out))
+        return 0
 
     # one C call per step, its arguments marshalled once per copy of W_sub (a drafting loop
     # repeats the same call; fr.fr_draft_topk re-checks every tensor on every call)
@@ -215,6 +239,16 @@ def main() -> int:
                                                           token_ids=ids256, logp=lp256), 100, 10, V_sub, d, cb.M)
     cfgs["batched_M128"] = leg(lambda i: fr.fr_draft_topk(H256[:128], copies[i % N_COPIES], idx_map, k, ws256,
                                                           token_ids=ids256[:128], logp=lp256[:128]), 100, 10, V_sub, d, 128)
+    # the same two shapes with the products alone (no softmax, no top-k), and through the chunked
+    # kernel (slabs of 128 rows of H, one pass over W_sub per slab): what the block kernel replaced
+    from paper_2502_14856_amd.binding import Tuning
+    for name, rows_h in (("batched_M256", cb.M), ("batched_M128", 128)):
+        for tag, tun in (("products_only", Tuning(stream_only=1)), ("chunked_kernel", Tuning(chunked_only=1))):
+            cfgs[f"{name}_{tag}"] = leg(lambda i: fr.fr_draft_topk(H256[:rows_h], copies[i % N_COPIES], idx_map, k, ws256,
+                                                                   token_ids=ids256[:rows_h], logp=lp256[:rows_h],
+                                                                   tuning=tun), 60, 6, V_sub, d, rows_h)
+    cfgs["full_vocab_M256"] = leg(lambda i: fr.fr_full_topk(H256, W_full, k, ws256, token_ids=ids256, logp=lp256),
+                                  30, 3, V, d, cb.M)
     cfgs["full_vocab_M64"] = leg(lambda i: fr.fr_full_topk(H256[:64], W_full, k, ws256, token_ids=ids256[:64],
                                                            logp=lp256[:64]), 50, 5, V, d, 64)
     # Qwen-2.5-7B-shaped: d = 3584, V_sub = 32768 of V = 152064, M = 60 (six draft depths batched)
@@ -230,7 +264,8 @@ def main() -> int:
     del Wq
     cfgs["note"] = ("cold rotation over >= 1 GiB of distinct weights per leg (windows of the five W_sub copies or of "
                     "W_full); back-to-back calls between two events; hbm_frac = rows*d*2 bytes / time / 8 TB/s; "
-                    "mfma_bf16_frac = 2*M*rows*d flops / time / 2.5 PFLOP/s; the batched and Qwen-shaped legs "
+                    "mfma_bf16_frac = 2*M*rows*d flops / time / 2.5 PFLOP/s; more than 64 rows of H run in the block "
+                    "kernel (one pass over W for up to 256 rows); the batched and Qwen-shaped legs "
                     "draw their hidden states (and the Qwen-shaped weights) from a seeded generator on the GPU")
 
     # ---- the glue of a draft phase (Section 2: beam search, depth 6, 60 draft tokens; width 10)
