@@ -295,7 +295,8 @@ fr_status fr_draft_topk_tiled(const void *H, int64_t M, int64_t d, const void *W
  *   fr_count_tokens  counts[t] += occurrences of t in tokens[0..n_tokens); ids outside [0, V)
  *                    are skipped and *dev_error_flag (optional) is set.  `counts` (int64 [V])
  *                    accumulates over calls: zero it before the first one.  `tokens` must be
- *                    16-byte aligned.
+ *                    16-byte aligned.  V <= 2^22 and n_tokens below 2^32 per share of the stream
+ *                    (one share per two compute units at V = 128256), else FR_ERR_UNSUPPORTED.
  *   fr_rank_tokens   freq_ranked_ids[0..V) = all ids by count descending, equal counts by
  *                    lower id (counts must be >= 0).  V <= 2^22, else FR_ERR_UNSUPPORTED.
  * All device pointers; asynchronous on `stream`.

@@ -489,6 +489,7 @@ fr_status fr_count_tokens(const int32_t *tokens, int64_t n_tokens, int64_t V, in
     if (!counts || (!tokens && n_tokens > 0) || n_tokens < 0 || V < 1 || V > INT32_MAX) return FR_ERR_INVALID_ARG;
     if (tokens && !aligned16(tokens)) return FR_ERR_ALIGNMENT;
     if ((reinterpret_cast<uintptr_t>(counts) & 7u) != 0) return FR_ERR_ALIGNMENT;
+    if (V > (1 << 22)) return FR_ERR_UNSUPPORTED;   // as the ranking: vocabularies, not hash spaces
     if (n_tokens == 0) return FR_OK;
     return launch_count_tokens(tokens, n_tokens, static_cast<int>(V), reinterpret_cast<unsigned long long *>(counts),
                                dev_error_flag, static_cast<hipStream_t>(stream));

@@ -693,8 +693,7 @@ fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hip
     a.tiles = (p.V_rows + kTileRows - 1) / kTileRows;
     a.steps = (a.d8 + kLanesAlongD - 1) / kLanesAlongD;
 
-    // Split d between wavefronts until every compute unit has a workgroup, as far as
-    // the number of steps allows.
+    // Wavefronts that share a tile and split d between them (see the rule below).
     int KS = 1;
     if (variant == kSkewVariant) {
         if (t && t->ksplit > 1) return FR_ERR_INVALID_ARG;
@@ -706,7 +705,15 @@ fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hip
             const int zr = (waves / ks) * kTileRows;
             return (p.V_rows + zr - 1) / zr;
         };
-        while (KS < waves && KS * 2 <= a.steps && passes_for(KS) < cus) KS *= 2;
+        // Measured rule (d = 4096, 256 compute units): while the passes do not fill three quarters of
+        // the compute units, halve them; once there is a pass for every compute unit, two half-size
+        // passes per workgroup stream faster than one (-0.5 us at 32768 rows, -1.5 us at 65536 and
+        // 128256, -6 us at 49152, where one-tile passes leave half the device idle in a second round).
+        if (passes_for(1) >= cus) {
+            if (2 <= waves && 4 <= a.steps) KS = 2;
+        } else {
+            while (KS < waves && KS * 2 <= a.steps && 4 * passes_for(KS) < 3 * cus) KS *= 2;
+        }
     }
     a.KS = KS;
     a.steps_per_split = (a.steps + KS - 1) / KS;

@@ -179,6 +179,7 @@ def test_token_statistics_reject_bad_arguments():
     assert L.fr_count_tokens(0x1004, 10, 100, 0x2000, None, None) == ALIGN
     assert L.fr_count_tokens(0x1000, 10, 100, 0x2004, None, None) == ALIGN
     assert L.fr_count_tokens(0x1000, 0, 100, 0x2000, None, None) == 0          # nothing to do, nothing launched
+    assert L.fr_count_tokens(0x1000, 10, (1 << 22) + 1, 0x2000, None, None) == UNSUPPORTED
     assert L.fr_rank_tokens(0, 100, 0x2000, None) == INVALID
     assert L.fr_rank_tokens(0x1000, 0, 0x2000, None) == INVALID
     assert L.fr_rank_tokens(0x1000, (1 << 22) + 1, 0x2000, None) == UNSUPPORTED
