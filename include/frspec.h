@@ -95,7 +95,7 @@ size_t fr_workspace_bytes(int64_t M, int64_t d, int64_t V_rows, int32_t k);
 
 /*
  * Prepares a freshly allocated workspace: clears the arrival counters of the single-launch
- * kernels and marks every record of the result mailboxes empty (about 8.5 MiB is written).
+ * kernels and marks every record of the result mailboxes empty (about 17 MiB is written).
  * Call once per workspace before its first use,
  * and again if a call using it was ever abandoned mid-flight.  Every completed call
  * leaves the workspace ready for the next one.  Calls that share a workspace must be

@@ -61,9 +61,9 @@ struct HeadProblem {
 };
 
 constexpr size_t kWorkspaceHeaderBytes = 512;
-// Result mailbox of the single-launch merge: 128 rows of H x (16 list positions + 1
+// Result mailbox of the single-launch merge: 256 rows of H x (16 list positions + 1
 // statistics record) x 512 workgroups, 8 bytes each, all ones while empty.
-constexpr int kMailRows = 128, kMailK = 16;   // rows of H and list positions with records
+constexpr int kMailRows = 256, kMailK = 16;   // rows of H and list positions with records
 constexpr size_t kMailRecBytes = (size_t)kMailRows * kMailK * 512u * 8u;
 constexpr size_t kMailStBytes = (size_t)kMailRows * 512u * 8u;
 constexpr size_t kStepRecBytes = 16u * 16u * 8u;   // one record per (row of H, list position)

@@ -61,7 +61,7 @@ def test_workspace_bytes_is_pure_host_arithmetic():
 
 
 def _draft(H=0x1000, M=10, d=4096, W=0x2000, idx=0, V=32768, k=10, ids=0x3000, lp=0x4000,
-           ws=0x5000, ws_bytes=1 << 24):
+           ws=0x5000, ws_bytes=1 << 26):
     return fr.lib().fr_draft_topk(H, M, d, W, idx, V, k, ids, lp, ws, ws_bytes, None)
 
 
@@ -90,8 +90,8 @@ def test_draft_topk_rejects_bad_arguments_before_any_launch():
 
 def test_full_topk_and_logits_reject_bad_arguments():
     L = fr.lib()
-    assert L.fr_full_topk(0, 1, 64, 0x2000, 100, 1, 0x3000, 0x4000, 0x5000, 1 << 24, None) == INVALID
-    assert L.fr_full_topk(0x1000, 1, 64, 0x2000, 100, 101, 0x3000, 0x4000, 0x5000, 1 << 24, None) == INVALID
+    assert L.fr_full_topk(0, 1, 64, 0x2000, 100, 1, 0x3000, 0x4000, 0x5000, 1 << 26, None) == INVALID
+    assert L.fr_full_topk(0x1000, 1, 64, 0x2000, 100, 101, 0x3000, 0x4000, 0x5000, 1 << 26, None) == INVALID
     assert L.fr_draft_logits(0x1000, 1, 64, 0x2000, 100, 0, None) == INVALID
     assert L.fr_draft_logits(0x1001, 1, 64, 0x2000, 100, 0x3000, None) == ALIGN
 
@@ -100,7 +100,7 @@ def test_tuned_entry_validates_knobs():
     t = Tuning()
     t.path = 7
     st = fr.lib().fr_draft_topk_tuned(0x1000, 10, 4096, 0x2000, 0, 32768, 10, 0x3000, 0x4000,
-                                      0x5000, 1 << 24, None, ctypes.byref(t))
+                                      0x5000, 1 << 26, None, ctypes.byref(t))
     assert st == INVALID
 
 

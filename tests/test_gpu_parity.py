@@ -318,20 +318,21 @@ def test_workspace_reuse_with_changing_inputs_sees_no_stale_partials():
 
 
 def test_one_workspace_across_changing_shapes_leaves_the_mailbox_empty():
-    # The single-launch merge (skinny kernel, and the chunked kernel up to 128 rows of H)
+    # The single-launch merge (skinny kernel, chunked kernel up to 128 rows of H, block kernel up to 256)
     # passes results through self-validating records that must all be empty again when a
     # call ends, whatever M, k, the kernel and the number of workgroups were; a record left
     # behind would be taken for a result by a later call.
     _say("workspace reuse, changing shapes")
     W, _, r = _case(9000, 256, 16, 21)
-    ws = fr.new_workspace(128, 256, 9000, 16)
+    ws = fr.new_workspace(256, 256, 9000, 16)
     W_d, r_d = to_dev_bf16(W), to_dev_i32(r)
     g = np.random.default_rng(22)
     shapes = [(10, 10, 4096, {}), (3, 16, 9000, {}), (16, 1, 100, {}), (10, 10, 4096, dict(grid=5)),
               (1, 7, 2048, dict(ksplit=2)), (12, 12, 6000, {}), (10, 10, 4096, dict(path=1)), (16, 16, 9000, {}),
               (40, 10, 4096, {}), (10, 10, 4096, dict(path=2)), (64, 16, 9000, {}), (17, 3, 300, {}),
               (40, 10, 4096, dict(no_mailbox=1)), (33, 1, 9000, dict(grid=7)), (100, 10, 9000, {}),
-              (128, 16, 4096, {}), (90, 5, 9000, dict(grid=9)), (10, 10, 4096, {})]
+              (128, 16, 4096, {}), (90, 5, 9000, dict(grid=9)), (10, 10, 4096, {}), (256, 10, 9000, {}),
+              (200, 16, 4096, dict(grid=6)), (130, 3, 700, {}), (10, 10, 4096, {})]
     for rep in range(2):
         for M, k, V_sub, knobs in shapes:
             H = f32_to_bf16_bits(g.standard_normal((M, 256)).astype(np.float32))
@@ -346,7 +347,7 @@ def test_one_workspace_across_changing_shapes_leaves_the_mailbox_empty():
             ids_g, lp_g = fr.fr_draft_topk(to_dev_bf16(H), W_g, idx_g, k, ws, tuning=t)
             _sync()
             check_topk_against_oracle(ids_g.cpu().numpy(), lp_g.cpu().numpy(), z_o, idx_o, ids_o, lp_o)
-            mail = ws[512:512 + (128 * 16 + 128) * 512 * 8].cpu().numpy()
+            mail = ws[512:512 + (256 * 16 + 256) * 512 * 8].cpu().numpy()
             assert (mail == 0xFF).all(), (M, k, V_sub, knobs)
             head = ws[:512].cpu().numpy().view(np.uint32)
             assert head[1] == 0      # no wait ever timed out
