@@ -260,7 +260,6 @@ __global__ __launch_bounds__(kBlockThreads) void block_kernel(BlockArgs a) {
                 h_store(1, 1);
                 h_issue(1, 2 * i + 3);
             }
-            __builtin_amdgcn_sched_barrier(0);
             products(st0, 0);
             __builtin_amdgcn_sched_barrier(0);
             __syncthreads();
@@ -271,7 +270,6 @@ __global__ __launch_bounds__(kBlockThreads) void block_kernel(BlockArgs a) {
                 h_store(0, 0);
                 h_issue(0, 2 * i + 4);
             }
-            __builtin_amdgcn_sched_barrier(0);
             products(st1, 1);
             __builtin_amdgcn_sched_barrier(0);
         };
