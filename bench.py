@@ -247,6 +247,19 @@ def main() -> int:
             cfgs[f"{name}_{tag}"] = leg(lambda i: fr.fr_draft_topk(H256[:rows_h], copies[i % N_COPIES], idx_map, k, ws256,
                                                                    token_ids=ids256[:rows_h], logp=lp256[:rows_h],
                                                                    tuning=tun), 60, 6, V_sub, d, rows_h)
+    # context only: the ROCm library GEMM behind torch.matmul on the same two shapes (logits written
+    # out as bf16, no softmax, no top-k), and the three library kernels a framework would chain
+    def _library(rows_h):
+        Hl = H256[:rows_h]
+        zl = torch.empty((rows_h, V_sub), dtype=torch.bfloat16, device="cuda")
+        t_mm = timed(lambda i: torch.matmul(Hl, copies[i % N_COPIES].t(), out=zl), 60, 6)
+        def chain(i):
+            z = torch.matmul(Hl, copies[i % N_COPIES].t()).float()
+            return torch.topk(torch.log_softmax(z, dim=1), k, dim=1)
+        t_chain = timed(chain, 30, 3)
+        return {"library_gemm_only_us": t_mm * 1e6, "library_gemm_log_softmax_topk_us": t_chain * 1e6}
+    cfgs["batched_M256"].update(_library(cb.M))
+    cfgs["batched_M128"].update(_library(128))
     cfgs["full_vocab_M256"] = leg(lambda i: fr.fr_full_topk(H256, W_full, k, ws256, token_ids=ids256, logp=lp256),
                                   30, 3, V, d, cb.M)
     cfgs["full_vocab_M64"] = leg(lambda i: fr.fr_full_topk(H256[:64], W_full, k, ws256, token_ids=ids256[:64],

@@ -411,6 +411,7 @@ fr_status prepare_block_kernels() {
 
 bool block_kernel_serves(int M, int d, int k) {
     if (M <= kBlockMinM - 1 || M > kBlockMaxM || (d % 128) != 0 || k > kSmallKMax) return false;
+    if ((long long)M * d * 2 > (1ll << 32)) return false;   // H is addressed with 32-bit byte offsets
     return BlockLds(tiles_for(M), k).total <= kLdsBudget - kStaticLdsReserve;
 }
 
