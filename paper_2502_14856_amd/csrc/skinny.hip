@@ -165,6 +165,8 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     constexpr int ZR_MAX = FOLD_WAVES * kTileRows;   // local rows that the fold's lanes cover
     // four rows of H per folding wavefront only where two would take a second round
     constexpr bool kQuadFold = !SKEW && MT > 2 * FOLD_WAVES;
+    // the default build also carries the fold for passes of 64 rows (two wavefronts per tile)
+    constexpr bool kHalfFold = MFMA && !TILED && !SKEW && WAVES == 8 && !kQuadFold;
     constexpr int kStep16 = kLanesAlongD;        // 16-byte chunks per row per step
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -474,8 +476,22 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
             const bool last = p + G >= a.passes;
             const FoldSink out{!last ? FoldTo::kLds : (mailbox ? FoldTo::kMailbox : FoldTo::kPartials),
                                part, a.mail, (int)blockIdx.x, run_ms, run_val, run_id};
-            if (SKEW && wave >= FOLD_WAVES) {
-                // the ninth wavefront only streams
+            bool folded = false;
+            if constexpr (kHalfFold) {
+                // two wavefronts per tile: a pass is 64 rows, and a fold laid out for 64 rows has half the
+                // logits per lane of the one laid out for 128 (of which half the lanes would hold none)
+                if (KS == 2) {
+                    if (p == first_pass)
+                        fold_pass<ZR_MAX / 2, false, false, false>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, 0, a.M,
+                                                                   wave, FOLD_WAVES, row_of, out, &s_select[wave]);
+                    else
+                        fold_pass<ZR_MAX / 2, true, false, false>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, 0, a.M,
+                                                                  wave, FOLD_WAVES, row_of, out, &s_select[wave]);
+                    folded = true;
+                }
+            }
+            if (folded || (SKEW && wave >= FOLD_WAVES)) {
+                // (done; or the ninth wavefront, which only streams)
             } else if (p == first_pass) {
                 fold_pass<ZR_MAX, false, SKEW, kQuadFold>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, 0, a.M, wave,
                                                FOLD_WAVES, row_of, out, &s_select[wave]);
