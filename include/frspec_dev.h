@@ -38,9 +38,6 @@ typedef struct fr_tuning {
                             with every kernel still ending normally */
     int32_t chunked_only; /* 1 = more than 64 rows of H also go to the chunked kernel, in slabs of up to
                             128 rows with one pass over W per slab (the path before the block kernel) */
-    int32_t unbounded_end; /* 1 = the skinny kernel folds the last pass of every workgroup like the
-                            others and merges all lists at the end, also where the bounded end
-                            (a bound from the other workgroups' earlier passes) applies */
     void *trace;         /* optional device buffer of 8 * 512 int64: every workgroup of a
                             contraction kernel records 100 MHz timestamps of its phases there */
 } fr_tuning;

@@ -31,7 +31,7 @@ class Tuning(ctypes.Structure):
                 ("grid", ctypes.c_int32), ("stream_only", ctypes.c_int32),
                 ("skew", ctypes.c_int32), ("no_mailbox", ctypes.c_int32),
                 ("spin_limit", ctypes.c_int32), ("chunked_only", ctypes.c_int32),
-                ("unbounded_end", ctypes.c_int32), ("trace", ctypes.c_void_p)]
+                ("trace", ctypes.c_void_p)]
 
 
 _lib = None

@@ -28,14 +28,13 @@ struct WorkspaceLayout {
 };
 
 // Scratch of fr_draft_topk_static, the entry point for callers that cannot allocate: one
-// workspace for up to kStaticRows rows of H and k <= kStaticK (header, a result mailbox of 48 rows
-// of records, which is what the skinny kernel uses for up to 16 rows of H, the plain partial
-// arrays; about 4.4 MiB), held by every device the library runs on until the
+// workspace for up to kStaticRows rows of H and k <= kStaticK (header, a 16-row result mailbox,
+// the plain partial arrays; about 2.2 MiB), held by every device the library runs on until the
 // process ends.  The array's name is a host-side stand-in, not a device address: host code
 // uses the address that hipGetSymbolAddress returns for the current device (each device has
 // its own copy), kept in DeviceState::scratch.
-constexpr int kStaticRows = 16, kStaticK = 16, kStaticMailRows = 48;
-constexpr size_t kStaticScratchBytes = WorkspaceLayout(kStaticRows, kStaticK, kStaticMailRows).total;
+constexpr int kStaticRows = 16, kStaticK = 16;
+constexpr size_t kStaticScratchBytes = WorkspaceLayout(kStaticRows, kStaticK, kStaticRows).total;
 }  // namespace
 }  // namespace frspec
 
@@ -47,7 +46,7 @@ namespace {
 // Header zero, every mailbox record empty (all ones): what fr_workspace_init does for a caller's
 // workspace.  Synchronous, on the null stream.
 fr_status prepare_scratch(void *ptr) {
-    constexpr size_t mail = WorkspaceLayout(kStaticRows, kStaticK, kStaticMailRows).ms_off - kWorkspaceHeaderBytes;
+    constexpr size_t mail = WorkspaceLayout(kStaticRows, kStaticK, kStaticRows).ms_off - kWorkspaceHeaderBytes;
     fr_status st = launch_fill_u32(static_cast<unsigned *>(ptr), kWorkspaceHeaderBytes / 4, 0u, nullptr);
     if (st != FR_OK) return st;
     st = launch_fill_u32(reinterpret_cast<unsigned *>(static_cast<char *>(ptr) + kWorkspaceHeaderBytes), mail / 4,
@@ -130,8 +129,7 @@ fr_status head_topk(const void *H, int64_t M, int64_t d, const void *W, const in
     if (st != FR_OK) return st;
     if (!token_ids || !logp || !workspace) return FR_ERR_INVALID_ARG;
     if (!aligned16(workspace)) return FR_ERR_ALIGNMENT;
-    // (a short mailbox serves the skinny kernel's rows only: 16 of H, in 48 rows of records)
-    if (mail_rows < kMailRows && M > kSkinnyMaxM) return FR_ERR_UNSUPPORTED;
+    if (M > mail_rows && mail_rows < kMailRows) return FR_ERR_UNSUPPORTED;   // (a short mailbox serves few rows)
     const WorkspaceLayout wl(M, k, mail_rows);
     if (workspace_bytes < wl.total) return FR_ERR_WORKSPACE;
     if (tuning && (tuning->path < 0 || tuning->path > 3 || tuning->grid < 0 ||
@@ -153,7 +151,6 @@ fr_status head_topk(const void *H, int64_t M, int64_t d, const void *W, const in
     p.ws.ticket = reinterpret_cast<unsigned *>(ws);
     p.ws.mail_rec = reinterpret_cast<unsigned long long *>(ws + wl.mail_rec_off);
     p.ws.mail_st = reinterpret_cast<unsigned long long *>(ws + wl.mail_st_off);
-    p.ws.mail_rows = mail_rows;
     p.ws.step_rec = reinterpret_cast<unsigned long long *>(ws + wl.step_rec_off);
     p.step = step;
     p.ws.part_ms = reinterpret_cast<float *>(ws + wl.ms_off);
@@ -372,7 +369,7 @@ fr_status fr_draft_topk_static(const void *H, int64_t M, int64_t d, const void *
     const DeviceState *st = device_state();
     if (!st || !st->scratch) return FR_ERR_HIP;
     return head_topk(H, M, d, W_sub, idx_map, V_sub, k, token_ids, logp, st->scratch, kStaticScratchBytes, stream,
-                     nullptr, false, nullptr, nullptr, kStaticMailRows);
+                     nullptr, false, nullptr, nullptr, kStaticRows);
 }
 
 fr_status fr_draft_topk_tuned(const void *H, int64_t M, int64_t d, const void *W_sub,

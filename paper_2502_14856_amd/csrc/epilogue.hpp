@@ -65,7 +65,6 @@ struct Mailbox {
     unsigned long long *rec;
     unsigned long long *st;
 };
-constexpr int kMailLateRow0 = 16, kMailFinRow0 = 32;   // bounded end: mailbox rows of the late lists and the final records
 constexpr int kStepRows = 16;                 // rows of H whose results the fused expansion collects
 constexpr unsigned long long kMailEmpty = ~0ull;
 constexpr unsigned kMailSpinLimit = 1u << 20;   // rounds of about a microsecond before giving up
@@ -90,7 +89,6 @@ __device__ __forceinline__ float mail_lo_f32(unsigned long long r) {
 
 // Blocks the wavefront until its outstanding stores have been acknowledged.
 __device__ __forceinline__ void wait_stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-
 
 // Arrival words at the start of the workspace.  Two arrival counters take turns from call
 // to call (`parity` says whose turn it is), each on a cache line of its own.
@@ -177,18 +175,6 @@ __device__ __forceinline__ void write_no_result(int first, int stride, int M, in
 __device__ __forceinline__ int merger_count(int G, int M) {
     int R = G < M ? G : M;
     return R < kMaxMergers ? R : kMaxMergers;
-}
-
-// The fixed mergers of the mailbox paths: every 8th workgroup while there are enough (workgroups
-// are dealt to the 8 compute dies in turn, so these share the first die), counted from the END of
-// the grid: workgroups start in order, so once the R mergers are on the machine everything
-// else they wait for is running or done, and waits for nothing itself.  Returns the merger
-// number of workgroup b (it merges rows r, r + R, ...), or -1.
-__device__ __forceinline__ int mailbox_merger_index(int G, int R, int b) {
-    const int spread = 8 * (R - 1) < G ? 8 : 1;
-    const int top = (G - 1) / spread * spread;   // the last workgroup that can be a merger
-    const int r = (top - b) / spread;
-    return (b > top || b % spread != 0 || r >= R) ? -1 : r;
 }
 
 // Where one row of H keeps its running state in LDS, and where its logits of the
@@ -332,9 +318,7 @@ __device__ __forceinline__ void lds_words(const T *p, T (&out)[C]) {
 // Where a fold puts its results: the workgroup's running state in LDS, or, on the
 // workgroup's last pass, straight into the workspace (slot g of the partials, or of the
 // mailbox).
-// kLate belongs to the bounded end (bounded.hpp): the list goes to the row's late-list records and
-// the statistics to its final statistics record.
-enum class FoldTo : int { kLds = 0, kPartials = 1, kMailbox = 2, kLate = 3 };
+enum class FoldTo : int { kLds = 0, kPartials = 1, kMailbox = 2 };
 struct FoldSink {
     FoldTo to;
     Partials part;
@@ -346,8 +330,6 @@ struct FoldSink {
     __device__ __forceinline__ void entry(int m, int k, int slot, float v, int id) const {
         if (to == FoldTo::kMailbox) {
             publish(mail.rec + mail_rec_index(m, slot, g), mail_pack(v, (unsigned)id));
-        } else if (to == FoldTo::kLate) {
-            publish(mail.rec + mail_rec_index(kMailLateRow0 + m, slot, g), mail_pack(v, (unsigned)id));
         } else if (to == FoldTo::kPartials) {
             publish(part.val + part_index(m * k + slot, g), v);
             publish(part.id + part_index(m * k + slot, g), id);
@@ -359,8 +341,6 @@ struct FoldSink {
     __device__ __forceinline__ void stats(int m, float mx, float S) const {
         if (to == FoldTo::kMailbox) {
             publish(mail.st + mail_st_index(m, g), mail_pack_stats(mx, S));
-        } else if (to == FoldTo::kLate) {
-            publish(mail.rec + mail_rec_index(kMailFinRow0 + m, 0, g), mail_pack_stats(mx, S));
         } else if (to == FoldTo::kPartials) {
             publish(part.ms + part_index(m * 2, g), mx);
             publish(part.ms + part_index(m * 2 + 1, g), S);

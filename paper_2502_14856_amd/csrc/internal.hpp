@@ -22,7 +22,6 @@ struct WorkspaceView {
     unsigned *ticket;
     unsigned long long *mail_rec;   // self-validating result records (single-launch merge)
     unsigned long long *mail_st;
-    int mail_rows;                  // rows of mail_rec (each kMailK list positions x 512 workgroups)
     unsigned long long *step_rec;   // hand-over records of the fused beam-search expansion
     float *part_ms;
     float *part_val;

@@ -22,7 +22,6 @@
 //     and write the outputs (for k <= 16 through self-validating mailbox records).
 // For small vocabularies several wavefronts share a tile and split d between them
 // (KS > 1) so that every compute unit still has enough loads in flight.
-#include "bounded.hpp"
 #include "epilogue.hpp"
 #include "internal.hpp"
 
@@ -72,7 +71,6 @@ struct SkinnyArgs {
     float *logp;
     float *z_out;
     int z_ld;
-    int bounded;          // 1: the last pass of every workgroup is folded under a bound (see bounded.hpp)
     long long *trace;     // optional [gridDim.x][8] phase timestamps (100 MHz clock)
 };
 
@@ -162,7 +160,6 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     __shared__ int s_slot;
     __shared__ SelectScratch s_select[WAVES];
     __shared__ MergeScratch s_merge;
-    __shared__ BoundedScratch s_bounded;
     const Partials part = a.part;   // a local copy keeps the argument block itself in registers
 
     constexpr int ZR_MAX = FOLD_WAVES * kTileRows;   // local rows that the fold's lanes cover
@@ -170,9 +167,6 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     constexpr bool kQuadFold = !SKEW && MT > 2 * FOLD_WAVES;
     // the default build also carries the fold for passes of 64 rows (two wavefronts per tile)
     constexpr bool kHalfFold = MFMA && !TILED && !SKEW && WAVES == 8 && !kQuadFold;
-    // ... and the bounded end of the single-launch path
-    constexpr bool kBounded = kHalfFold;
-    const bool bounded = kBounded && a.bounded != 0;
     constexpr int kStep16 = kLanesAlongD;        // 16-byte chunks per row per step
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -378,8 +372,6 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
             }
         };
 
-        const bool last = p + G >= a.passes;   // the workgroup's last pass
-        unsigned row_bound = 0u;               // bounded end: the bound of this lane's row of H (high word of a key)
         if (groups > 0) {
             const int c_begin = s_begin * kStep16;
             int grp = g_first;
@@ -387,7 +379,7 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
             // group.  The scheduling barriers keep the refill where it is written: left
             // alone, the scheduler sinks all loads to the end of the body (shorter live
             // ranges) and the wavefront then waits for every load it has just issued.
-            auto steady = [&]() __attribute__((always_inline)) {
+            for (int it = 0; it < groups - 1; ++it) {
                 const int nxt = (grp + 1 == groups) ? 0 : grp + 1;
                 const int cg = c_begin + grp * (DEPTH * kStep16);
                 const unsigned nofs = (unsigned)nxt * kGroupBytes;
@@ -401,62 +393,27 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 grp = nxt;
-            };
-            bool streamed = false;
-            if constexpr (kBounded) {
-                if (bounded && last) {
-                    // The bounded end, in a copy of the loop of its own (every load and store
-                    // stays unconditional and counted, but for the wavefronts with a second row of
-                    // H).  First the early list goes out.  One group of steps before the end of the
-                    // stream a wavefront requests the heads of all early lists of its two rows of
-                    // H; they arrive ahead of the last stages of W and are turned into the rows'
-                    // bounds while those stages are on their way.  (The host admits the bounded
-                    // end only with at least two groups per wavefront.)
-                    post_early_list(a.mail, wave, a.M, a.k, (int)blockIdx.x, run_val, run_id);
-                    for (int it = 0; it < groups - 2; ++it) steady();
-                    const bool second_row = wave + WAVES < a.M;   // wave-uniform
-                    unsigned heads_lo[4], heads_hi[4] = {~0u, ~0u, ~0u, ~0u};
-                    request_heads(a.mail, min(wave, a.M - 1), G, heads_lo);
-                    if (second_row) request_heads(a.mail, wave + WAVES, G, heads_hi);
-                    steady();
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) asm volatile("" : "+v"(heads_lo[q]));
-                    row_bound = bound_from_heads(heads_lo, G, a.k);
-                    if (second_row) {
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) asm volatile("" : "+v"(heads_hi[q]));
-                        const unsigned b_hi = bound_from_heads(heads_hi, G, a.k);
-                        row_bound = (lane >> 5) ? b_hi : row_bound;
-                    }
-                    const int cg = c_begin + grp * (DEPTH * kStep16);
-#pragma unroll
-                    for (int u = 0; u < DEPTH; ++u) compute(wb[u], cg + u * kStep16);
-                    streamed = true;
-                }
             }
-            if (!streamed) {
-                for (int it = 0; it < groups - 1; ++it) steady();
-                // drain; the stages freed here start on the next pass of this workgroup
-                const int cg = c_begin + grp * (DEPTH * kStep16);
-                const bool has_next = !SKEW && p + G < a.passes;   // (the skewed build has one pass)
-                if (has_next) {
-                    id_next = request_id(p + G);
-                    row_offsets(p + G, wo);
-                    const unsigned nofs = (unsigned)g_first * kGroupBytes;
+            // drain; the stages freed here start on the next pass of this workgroup
+            const int cg = c_begin + grp * (DEPTH * kStep16);
+            const bool has_next = !SKEW && p + G < a.passes;   // (the skewed build has one pass)
+            if (has_next) {
+                id_next = request_id(p + G);
+                row_offsets(p + G, wo);
+                const unsigned nofs = (unsigned)g_first * kGroupBytes;
 #pragma unroll
-                    for (int u = 0; u < DEPTH; ++u) {
-                        compute(wb[u], cg + u * kStep16);
-                        __builtin_amdgcn_sched_barrier(0);
+                for (int u = 0; u < DEPTH; ++u) {
+                    compute(wb[u], cg + u * kStep16);
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                        for (int r = 0; r < kRowsPerLane; ++r)
-                            wb[u][r] = load_w(Wb, wo[r] + nofs + u * kStepBytes);
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                    asm volatile("" : "+v"(id_next));   // wait for it here, where the loads behind it are counted
-                } else {
-#pragma unroll
-                    for (int u = 0; u < DEPTH; ++u) compute(wb[u], cg + u * kStep16);
+                    for (int r = 0; r < kRowsPerLane; ++r)
+                        wb[u][r] = load_w(Wb, wo[r] + nofs + u * kStepBytes);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
+                asm volatile("" : "+v"(id_next));   // wait for it here, where the loads behind it are counted
+            } else {
+#pragma unroll
+                for (int u = 0; u < DEPTH; ++u) compute(wb[u], cg + u * kStep16);
             }
         }
         if (s_pipe_end < s_end) {
@@ -515,39 +472,15 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
             auto row_of = [&](int m) {
                 return FoldRow{z_lds + m * ZR, run_ms + 2 * m, run_val + m * a.k, run_id + m * a.k};
             };
-            // the last pass of the workgroup writes its result out instead of keeping it; with the
-            // bounded end the list of the passes before it is out already, and the last one is
-            // folded under the bound
+            // the last pass of the workgroup writes its result out instead of keeping it
+            const bool last = p + G >= a.passes;
             const FoldSink out{!last ? FoldTo::kLds : (mailbox ? FoldTo::kMailbox : FoldTo::kPartials),
                                part, a.mail, (int)blockIdx.x, run_ms, run_val, run_id};
             bool folded = false;
-            if constexpr (kBounded) {
-                if (bounded && last) {
-                    if (wave < a.M) {
-                        const int m = (lane >> 5) ? wave + WAVES : wave;
-                        const bool active = m < a.M;
-                        const bool done =
-                            KS == 2 ? fold_pair_bounded<ZR_MAX / 2>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, m, active,
-                                                                    row_bound, run_ms, a.mail, (int)blockIdx.x)
-                                    : fold_pair_bounded<ZR_MAX>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, m, active,
-                                                                row_bound, run_ms, a.mail, (int)blockIdx.x);
-                        if (!done) {
-                            // too many late survivors in one of the two rows: the k best of the pass
-                            // go out as late lists (the running lists are empty since the early
-                            // lists went out, the running statistics are not)
-                            const FoldSink late{FoldTo::kLate, part, a.mail, (int)blockIdx.x, run_ms, run_val, run_id};
-                            fold_pass<ZR_MAX, true, false, false>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, 0, a.M,
-                                                                  wave, FOLD_WAVES, row_of, late, &s_select[wave]);
-                            mark_rows_late(a.mail, m, active, (int)blockIdx.x);
-                        }
-                    }
-                    folded = true;
-                }
-            }
             if constexpr (kHalfFold) {
                 // two wavefronts per tile: a pass is 64 rows, and a fold laid out for 64 rows has half the
                 // logits per lane of the one laid out for 128 (of which half the lanes would hold none)
-                if (KS == 2 && !folded) {
+                if (KS == 2) {
                     if (p == first_pass)
                         fold_pass<ZR_MAX / 2, false, false, false>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, 0, a.M,
                                                                    wave, FOLD_WAVES, row_of, out, &s_select[wave]);
@@ -585,24 +518,20 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     const int R = merger_count(G, a.M);
     if (mailbox) {
         // Mailbox records announce themselves: nothing to wait for, nothing to count.  The
-        // mergers are fixed (mailbox_merger_index) and start polling for the others' records as
-        // soon as their own are out.
-        const int r = mailbox_merger_index(G, R, (int)blockIdx.x);
-        if (r < 0) return;
+        // mergers are fixed, every 8th workgroup while there are enough (workgroups are
+        // dealt to the 8 dies in turn, so these share the first die), counted from the END of
+        // the grid: workgroups start in order, so once the R <= 16 mergers are on the machine
+        // everything else they wait for is running or done, and waits for nothing itself.
+        // They start polling for the others' records as soon as their own are out.
+        const int spread = 8 * (R - 1) < G ? 8 : 1;
+        const int b = (int)blockIdx.x;
+        const int top = (G - 1) / spread * spread;   // the last workgroup that can be a merger
+        const int r = (top - b) / spread;
+        if (b > top || b % spread != 0 || r >= R) return;
         stamp(4);
         const unsigned spin = a.spin_limit ? a.spin_limit : kMailSpinLimit;
-        bool merged = false;
-        if constexpr (kBounded) {
-            if (bounded) {
-                merge_rows_bounded(a.mail, part, a.ticket + 1, G, r, R, a.M, a.k, a.token_ids, a.logp, &s_merge,
-                                   &s_bounded, &s_select[0], a.step.rec, spin,
-                                   a.trace ? a.trace + blockIdx.x * 8 : nullptr);
-                merged = true;
-            }
-        }
-        if (!merged)
-            merge_rows_mailbox<(WAVES >= 8 ? 8 : 4)>(a.mail, part, a.ticket + 1, G, r, R, a.M, a.k, a.token_ids, a.logp,
-                                                     &s_merge, &s_select[0], a.step.rec, spin);
+        merge_rows_mailbox<(WAVES >= 8 ? 8 : 4)>(a.mail, part, a.ticket + 1, G, r, R, a.M, a.k, a.token_ids, a.logp, &s_merge,
+                           &s_select[0], a.step.rec, spin);
         // the first merger also runs the beam-search expansion of the step, if one was asked for
         if (a.step.rec && r == 0 && wave == 0)
             expand_step_fused(a.step, a.M, a.k, reinterpret_cast<unsigned long long *>(s_select), a.ticket + 1, spin);
@@ -853,15 +782,6 @@ fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hip
         }
     }
     const int lds = lds_bytes(p.M, p.d, p.k, variant);
-
-    // The bounded end (bounded.hpp) serves the default build's single-launch mailbox path when every
-    // workgroup has the same number of passes, at least two (with one pass fewer a workgroup would
-    // look for its bounds before the others have sent out their early lists), every wavefront has
-    // at least two whole groups of steps,
-    // and the workspace's mailbox has the rows for the late lists and the final records.
-    a.bounded = variant == 0 && sink == Sink::kFusedTopk && p.k <= kSmallKMax && grid <= 4 * kWave &&
-                a.passes >= 2 * grid && a.passes % grid == 0 && p.ws.mail_rows >= kBoundedMailRows && (a.d8 % kLanesAlongD) == 0 &&
-                (a.steps % KS) == 0 && a.steps_per_split >= 2 * kVariants[0].depth && !(t && t->unbounded_end);
 
     const SkinnyKernel kern = select_kernel(variant, a.M, MT);
     if (!kern) return FR_ERR_INVALID_ARG;
