@@ -70,12 +70,14 @@ __global__ __launch_bounds__(kGlueThreads) void tree_select_kernel(
     const float *__restrict__ hist_score, const int *__restrict__ hist_token,
     const int *__restrict__ hist_parent, int N, int K, int *__restrict__ sel_index,
     int *__restrict__ sel_token, int *__restrict__ sel_parent, int *__restrict__ sel_depth,
-    unsigned char *__restrict__ tree_mask) {
+    unsigned char *__restrict__ tree_mask, int groups) {
     extern __shared__ u32x4 smem[];
     unsigned long long *keys = reinterpret_cast<unsigned long long *>(smem);   // [N + 2]
     int *posmap = reinterpret_cast<int *>(keys + ((N + 2) & ~1));              // [N]: position or -1
     int *par = posmap + N;                                                     // [N]: hist_parent
     __shared__ int chunk_before[kGlueChunks];   // selected entries before each 64-entry chunk
+    __shared__ unsigned long long s_bound;
+    __shared__ int s_survivors;
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     for (int i = tid; i < N; i += kGlueThreads) {
         keys[i] = make_key(key_hi_of(hist_score[i]), ~(unsigned)i);
@@ -89,6 +91,61 @@ __global__ __launch_bounds__(kGlueThreads) void tree_select_kernel(
     // rank[i] = number of better entries.  A short history is scanned by several threads per
     // entry (P of them share the keys between them), a long one by one thread per entry.
     int *rank = par + N;   // [N]
+    if (groups > 0) {
+        // Only "is it among the K best" is needed, not every entry's rank.  The entries fall into
+        // `groups` >= 2K groups (entry i in group i % groups); the K-th largest group maximum B is a
+        // lower bound of the K-th best key (K different groups hold a key that large), so only the
+        // entries at or above B (K plus some) are ranked, among themselves: groups^2 + (K + some)^2
+        // comparisons instead of N^2.
+        // (16-byte aligned: the three int arrays padded to a multiple of four ints)
+        unsigned long long *gmax = reinterpret_cast<unsigned long long *>(rank + N + ((4 - (3 * N) % 4) % 4));   // [groups + 2]
+        unsigned long long *surv = gmax + groups + 2;                                               // [N + 2]
+        int *grank = reinterpret_cast<int *>(surv + ((N + 2) & ~1));                                // [groups]
+        for (int g = tid; g < groups; g += kGlueThreads) {
+            unsigned long long best = 0ull;
+            for (int i = g; i < N; i += groups) best = max(best, keys[i]);
+            gmax[g] = best;
+            grank[g] = 0;
+        }
+        if (tid == 0) {
+            gmax[groups] = 0ull;
+            s_survivors = 0;
+        }
+        __syncthreads();
+        {
+            const int P = kGlueThreads / groups;   // threads per group maximum (groups divides 1024)
+            const int g = tid / P, part = tid - g * P;
+            const int per = groups / P;            // even: groups >= 2 P whenever P > 1, both powers of two
+            if (P == 1)
+                grank[g] = count_greater(gmax, groups, gmax[g]);
+            else
+                atomicAdd(&grank[g], count_greater(gmax + part * per, per, gmax[g]));
+        }
+        __syncthreads();
+        for (int g = tid; g < groups; g += kGlueThreads)
+            if (grank[g] == K - 1) s_bound = gmax[g];   // (the keys are all different: exactly one)
+        __syncthreads();
+        const unsigned long long B = s_bound;
+        for (int i = tid; i < N; i += kGlueThreads) {
+            const bool sv = keys[i] >= B;
+            rank[i] = sv ? 0 : K;
+            if (sv) surv[atomicAdd(&s_survivors, 1)] = keys[i];
+        }
+        __syncthreads();
+        const int ns = s_survivors;
+        if (tid < 2) surv[ns + tid] = 0ull;
+        __syncthreads();
+        int P = 1;
+        while (P < 16 && 2 * P * ns <= kGlueThreads) P *= 2;
+        for (int e = tid / P; e < ns; e += kGlueThreads / P) {
+            const int part = tid % P;
+            const int per = ((ns + P - 1) / P + 1) & ~1;
+            const int lo = part * per, hi = lo + per < ns ? lo + per : ns;
+            const unsigned long long mine = surv[e];
+            if (lo < hi) atomicAdd(&rank[(int)~(unsigned)mine], count_greater(surv + lo, hi - lo, mine));
+        }
+        __syncthreads();
+    } else {
     for (int i = tid; i < N; i += kGlueThreads) rank[i] = 0;
     __syncthreads();
     int P = 1;
@@ -104,6 +161,7 @@ __global__ __launch_bounds__(kGlueThreads) void tree_select_kernel(
         for (int i = tid; i < N; i += kGlueThreads) rank[i] = count_greater(keys, N, keys[i]);
     }
     __syncthreads();
+    }
     // selected = fewer than K better entries.  Entry i = tid + u * 1024 lies in chunk i / 64,
     // which one wavefront covers with one ballot.
     int before_in_chunk[kGluePerThread];
@@ -169,10 +227,10 @@ fr_status launch_beam_expand(const float *logp, const int *token_ids, int C, int
     return hip_status(hipGetLastError());
 }
 
-// up to 80 KiB + 16 B of dynamic LDS: above the default limit
+// up to ~125 KiB of dynamic LDS (4096 entries, with the bound's groups and survivor list): above the default limit
 fr_status prepare_glue_kernels() {
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(tree_select_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024) != hipSuccess) {
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024) != hipSuccess) {
         (void)hipGetLastError();
         return FR_ERR_HIP;
     }
@@ -182,10 +240,17 @@ fr_status prepare_glue_kernels() {
 fr_status launch_tree_select(const float *hist_score, const int *hist_token, const int *hist_parent, int N, int K,
                              int *sel_index, int *sel_token, int *sel_parent, int *sel_depth,
                              unsigned char *tree_mask, hipStream_t s) {
-    const size_t lds = ((size_t)((N + 2) & ~1)) * sizeof(unsigned long long) + 3 * (size_t)N * sizeof(int);
+    size_t lds = ((size_t)((N + 2) & ~1)) * sizeof(unsigned long long) + ((3 * (size_t)N + 3) & ~(size_t)3) * sizeof(int);
+    // groups of the bound: a power of two, at least 2K; where that leaves fewer than two entries
+    // per group on average the plain all-pairs ranking is as cheap
+    int groups = 64;
+    while (groups < 2 * K) groups *= 2;
+    if (groups > kGlueThreads || 2 * groups > N) groups = 0;
+    if (groups > 0)
+        lds += ((size_t)groups + 2 + (size_t)((N + 2) & ~1)) * sizeof(unsigned long long) + (size_t)groups * sizeof(int);
     if (!device_state()) return FR_ERR_HIP;   // (the per-device set-up raised this kernel's LDS limit)
     hipLaunchKernelGGL(tree_select_kernel, dim3(1), dim3(kGlueThreads), lds, s, hist_score, hist_token,
-                       hist_parent, N, K, sel_index, sel_token, sel_parent, sel_depth, tree_mask);
+                       hist_parent, N, K, sel_index, sel_token, sel_parent, sel_depth, tree_mask, groups);
     return hip_status(hipGetLastError());
 }
 

@@ -60,8 +60,12 @@ def _random_history(rng, n, quantised):
     return score, rng.integers(0, 128256, size=n).astype(np.int32), parent
 
 
+# (from 2K-and-more groups of at least two entries on, the selection goes through a bound and ranks
+# only the entries above it: 510/60, 610/60, 256/64 (exactly two per group), 300/60, 3000/300, 4096/...)
 @pytest.mark.parametrize("seed,n,K", [(0, 40, 12), (1, 610, 60), (2, 610, 60), (3, 100, 100), (4, 1, 1),
-                                      (5, 4096, 128), (6, 1500, 1024), (7, 33, 32)])
+                                      (5, 4096, 128), (6, 1500, 1024), (7, 33, 32), (8, 510, 60), (9, 256, 64),
+                                      (10, 300, 60), (11, 3000, 300), (12, 4096, 512), (13, 4095, 1),
+                                      (14, 255, 64), (16, 4096, 33)])
 def test_tree_select_matches_oracle_bit_for_bit(seed, n, K):
     _say("tree select", seed, n, K)
     rng = np.random.default_rng([20250214, 92, seed])
