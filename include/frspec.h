@@ -299,6 +299,9 @@ fr_status fr_draft_topk_tiled(const void *H, int64_t M, int64_t d, const void *W
  *                    (one share per two compute units at V = 128256), else FR_ERR_UNSUPPORTED.
  *   fr_rank_tokens   freq_ranked_ids[0..V) = all ids by count descending, equal counts by
  *                    lower id (counts must be >= 0).  V <= 2^22, else FR_ERR_UNSUPPORTED.
+ *                    Takes 20 V bytes + 25 KiB of temporary device memory from the stream-ordered
+ *                    allocator and returns it in stream order (a model-load step: the one call
+ *                    of this library that allocates; FR_ERR_HIP if the allocation fails).
  * All device pointers; asynchronous on `stream`.
  */
 fr_status fr_count_tokens(const int32_t *tokens, int64_t n_tokens, int64_t V, int64_t *counts,

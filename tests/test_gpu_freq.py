@@ -53,8 +53,10 @@ def test_count_tokens_accumulates_and_flags_bad_ids():
     assert np.array_equal(counts.cpu().numpy(), want)
 
 
+# ("edges": counts on both sides of every boundary between the count-magnitude buckets that the
+# ranking deals the ids into; "equal": one bucket holds everything)
 @pytest.mark.parametrize("V,kind", [(1, "zero"), (257, "ties"), (5000, "ties"), (128256, "zipf"), (152064, "ties"),
-                                    (4099, "big")])
+                                    (4099, "big"), (20011, "edges"), (70001, "equal"), (300000, "zipf")])
 def test_rank_tokens_matches_oracle(V, kind):
     _say("rank tokens", V, kind)
     rng = np.random.default_rng([20250214, 99, V])
@@ -62,6 +64,13 @@ def test_rank_tokens_matches_oracle(V, kind):
         counts = np.zeros(V, np.int64)
     elif kind == "ties":
         counts = rng.integers(0, 25, size=V).astype(np.int64)
+    elif kind == "edges":
+        e = rng.integers(0, 62, size=V)
+        mant = rng.integers(0, 33, size=V)
+        base = (np.int64(1) << e) + ((mant.astype(np.int64) << e) >> 5)
+        counts = np.maximum(base + rng.integers(-1, 2, size=V), 0).astype(np.int64)
+    elif kind == "equal":
+        counts = np.full(V, 5, np.int64)
     elif kind == "big":
         counts = rng.integers(0, 1 << 62, size=V).astype(np.int64)
         counts[::7] = counts[3]
