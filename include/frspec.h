@@ -12,7 +12,8 @@
  *
  * Conventions common to every call
  *   - All data pointers are DEVICE pointers into memory owned by the caller.
- *     The library allocates nothing and frees nothing.  Per-call state lives in the
+ *     The library allocates nothing and frees nothing (one exception, a model-load step:
+ *     fr_rank_tokens, see there).  Per-call state lives in the
  *     caller's workspace; what the library itself keeps, per device and for the life of
  *     the process, is the result of a one-time set-up (number of compute units, raised
  *     LDS limits of its kernels): see fr_init.
