@@ -364,7 +364,7 @@ struct FoldSink {
  * the bound (heavily tied values, or fewer than k populated groups): the caller then
  * takes the general path for both rows.
  */
-template <int ZR_MAX, bool WITH_RUN, bool WITH_EXTRA = false>
+template <int ZR_MAX, bool WITH_RUN, bool WITH_EXTRA = false, bool B32 = false>
 __device__ __forceinline__ bool fold_pair_fast(const float *z_lds, int z_row_stride, int m_base, int KS,
                                                int z_slice_stride, const int *ids_pass, int n_valid, int k, int m,
                                                bool active, const FoldSink &out, SelectScratch *sc) {
@@ -446,7 +446,8 @@ __device__ __forceinline__ bool fold_pair_fast(const float *z_lds, int z_row_str
     unsigned lm = hi[0];
 #pragma unroll
     for (int c = 1; c < CPL; ++c) lm = max(lm, hi[c]);
-    const unsigned L = row16_kth_largest_u32(max_xor16_u32(lm), k);
+    // (groups: the 16 lane pairs (l, l ^ 16) of the half; from k = 11 on every lane of its own)
+    const unsigned L = B32 ? half32_kth_largest_u32(lm, k) : row16_kth_largest_u32(max_xor16_u32(lm), k);
 
     // survivors of each half, packed into its 32 scratch slots
     sc->key[lane] = 0ull;
@@ -493,7 +494,7 @@ __device__ __forceinline__ bool fold_pair_fast(const float *z_lds, int z_row_str
  * list when WITH_RUN.  A group is one lane, so the 16 group maxima already sit in the 16
  * lanes of the row.  Up to 32 survivors per row, two per lane when they are ranked.
  */
-template <int ZR_MAX, bool WITH_RUN>
+template <int ZR_MAX, bool WITH_RUN, bool B32 = false>
 __device__ __forceinline__ bool fold_quad_fast(const float *z_lds, int z_row_stride, int m_base, int KS,
                                                int z_slice_stride, const int *ids_pass, int n_valid, int k, int m,
                                                bool active, const FoldSink &out, SelectScratch *sc) {
@@ -552,10 +553,21 @@ __device__ __forceinline__ bool fold_quad_fast(const float *z_lds, int z_row_str
         hi[CPL - 1] = run_i != INT_MAX ? key_hi_of(run_v) : 0u;
         lo[CPL - 1] = ~(unsigned)run_i;
     }
-    unsigned lm = hi[0];
+    unsigned L;
+    if constexpr (B32) {
+        // 32 groups: the two halves of the lane's logits (the entry of the running list joins the second)
+        unsigned la = hi[0], lb = hi[C / 2];
 #pragma unroll
-    for (int c = 1; c < CPL; ++c) lm = max(lm, hi[c]);
-    const unsigned L = row16_kth_largest_u32(lm, k);
+        for (int c = 1; c < C / 2; ++c) la = max(la, hi[c]);
+#pragma unroll
+        for (int c = C / 2 + 1; c < CPL; ++c) lb = max(lb, hi[c]);
+        L = row16x2_kth_largest_u32(la, lb, k);
+    } else {
+        unsigned lm = hi[0];
+#pragma unroll
+        for (int c = 1; c < CPL; ++c) lm = max(lm, hi[c]);
+        L = row16_kth_largest_u32(lm, k);
+    }
 
     // survivors of each row, packed into its 32 scratch slots
     sc->key[lane] = 0ull;
@@ -622,7 +634,7 @@ __device__ __noinline__ void fold_row_general(FoldRow row, int KS, int z_slice_s
  * round trips, and the four-row one is the longer chain: QUAD pays off where the rows
  * would otherwise take more than one round per wavefront.
  */
-template <int ZR_MAX, bool WITH_RUN, bool WITH_EXTRA = false, bool QUAD = false, typename RowOf>
+template <int ZR_MAX, bool WITH_RUN, bool WITH_EXTRA = false, bool QUAD = false, bool B32 = false, typename RowOf>
 __device__ __forceinline__ void fold_pass(const float *z_lds, int z_row_stride, int KS, int z_slice_stride,
                                           const int *ids_pass, int n_valid, int k, int m_base, int m_end, int wave,
                                           int waves, RowOf row_of, const FoldSink &out, SelectScratch *sc) {
@@ -634,7 +646,7 @@ __device__ __forceinline__ void fold_pass(const float *z_lds, int z_row_stride, 
             const int m0 = mb + 4 * wave;
             if (m0 >= m_end) break;
             const int m = m0 + (lane_id() >> 4);
-            if (fold_quad_fast<ZR_MAX, WITH_RUN>(z_lds, z_row_stride, m_base, KS, z_slice_stride, ids_pass, n_valid, k,
+            if (fold_quad_fast<ZR_MAX, WITH_RUN, B32>(z_lds, z_row_stride, m_base, KS, z_slice_stride, ids_pass, n_valid, k,
                                                  m, m < m_end, out, sc))
                 continue;
             for (int i = 0; i < 4 && m0 + i < m_end; ++i)
@@ -646,7 +658,7 @@ __device__ __forceinline__ void fold_pass(const float *z_lds, int z_row_stride, 
             const int m_lo = mb + wave, m_hi = mb + wave + waves;
             if (m_lo >= m_end) break;
             const int m = (lane_id() >> 5) ? m_hi : m_lo;
-            if (fold_pair_fast<ZR_MAX, WITH_RUN, WITH_EXTRA>(z_lds, z_row_stride, m_base, KS, z_slice_stride,
+            if (fold_pair_fast<ZR_MAX, WITH_RUN, WITH_EXTRA, B32>(z_lds, z_row_stride, m_base, KS, z_slice_stride,
                                                              ids_pass, n_valid, k, m, m < m_end, out, sc))
                 continue;
             fold_row_general<ZR_GEN, WITH_RUN>(row_of(m_lo), KS, z_slice_stride, ids_pass, n_valid, k, sc, out, m_lo);
@@ -990,7 +1002,7 @@ __device__ __forceinline__ void expand_step_fused(const StepArgs &st, int M, int
  * skipped), the survivors meet in LDS, and the first wavefront ranks them and writes
  * the outputs.  The records are emptied for the next call on the way.
  */
-template <int NW = 4>   // fetching wavefronts: 4 or 8, at most the wavefronts of the workgroup
+template <int NW = 4, bool B32 = false>   // NW fetching wavefronts: 4 or 8, at most the wavefronts of the workgroup
 __device__ __forceinline__ void merge_rows_mailbox(const Mailbox &mb, const Partials &P, unsigned *error, int G,
                                                    int first, int stride, int M, int k, int *token_ids,
                                                    float *logp, MergeScratch *ms, SelectScratch *sc,
@@ -1065,10 +1077,10 @@ __device__ __forceinline__ void merge_rows_mailbox(const Mailbox &mb, const Part
             float lmax = kNegInf;
 #pragma unroll
             for (int q = 0; q < HPL; ++q) lmax = fmaxf(lmax, lane + kWave * q < G ? mail_hi(head[q]) : kNegInf);
-            unsigned gm = key_hi_of(lmax);
-            gm = max_xor16_u32(gm);
-            gm = max_xor32_u32(gm);
-            const float bound = value_of_key_hi(row16_kth_largest_u32(gm, k));
+            // (from k = 11 on 32 groups, {g : g mod 32 = j})
+            unsigned gm = max_xor32_u32(key_hi_of(lmax));
+            const float bound = value_of_key_hi(B32 ? half32_kth_largest_u32(gm, k)
+                                                        : row16_kth_largest_u32(max_xor16_u32(gm), k));
 
             // ---- survivors among this wavefront's entries: not below the bound (a NaN
             // is not below anything, and ranks first like in the key order).  First all

@@ -347,12 +347,17 @@ __global__ __launch_bounds__(kBlockThreads) void block_kernel(BlockArgs a) {
                 };
                 const FoldSink out{!last ? FoldTo::kLds : (a.mailbox ? FoldTo::kMailbox : FoldTo::kPartials),
                                    a.part, a.mail, (int)blockIdx.x, run_ms, run_val, run_id};
-                if (p == (int)blockIdx.x)
-                    fold_pass<kTV, false, false, true>(z_all, kTV + kZPad, 1, 0, ids_lds, n_valid, a.k, m_base, m_end,
-                                                       wave, kBlockWaves, row_of, out, &s_select[wave]);
-                else
-                    fold_pass<kTV, true, false, true>(z_all, kTV + kZPad, 1, 0, ids_lds, n_valid, a.k, m_base, m_end,
-                                                      wave, kBlockWaves, row_of, out, &s_select[wave]);
+                auto fold_with = [&](auto b32) {   // (bound from 16 groups up to k = 10, from 32 beyond)
+                    constexpr bool B32 = decltype(b32)::value;
+                    if (p == (int)blockIdx.x)
+                        fold_pass<kTV, false, false, true, B32>(z_all, kTV + kZPad, 1, 0, ids_lds, n_valid, a.k, m_base,
+                                                                m_end, wave, kBlockWaves, row_of, out, &s_select[wave]);
+                    else
+                        fold_pass<kTV, true, false, true, B32>(z_all, kTV + kZPad, 1, 0, ids_lds, n_valid, a.k, m_base,
+                                                               m_end, wave, kBlockWaves, row_of, out, &s_select[wave]);
+                };
+                if (a.k >= kBound32FromK) fold_with(std::true_type{});
+                else fold_with(std::false_type{});
             }
         }
     }
@@ -367,8 +372,13 @@ __global__ __launch_bounds__(kBlockThreads) void block_kernel(BlockArgs a) {
         const int R = G < a.M ? G : a.M;
         if (gidx < G - R) return;
         stamp(4);
-        merge_rows_mailbox<8>(mb, part, a.ticket + 1, G, gidx - (G - R), R, a.M, a.k, a.token_ids, a.logp, &s_merge,
-                              &s_select[0], nullptr, a.spin_limit ? a.spin_limit : kMailSpinLimit);
+        const unsigned spin = a.spin_limit ? a.spin_limit : kMailSpinLimit;
+        if (a.k >= kBound32FromK)
+            merge_rows_mailbox<8, true>(mb, part, a.ticket + 1, G, gidx - (G - R), R, a.M, a.k, a.token_ids, a.logp,
+                                        &s_merge, &s_select[0], nullptr, spin);
+        else
+            merge_rows_mailbox<8, false>(mb, part, a.ticket + 1, G, gidx - (G - R), R, a.M, a.k, a.token_ids, a.logp,
+                                         &s_merge, &s_select[0], nullptr, spin);
         __syncthreads();
         stamp(5);
         return;

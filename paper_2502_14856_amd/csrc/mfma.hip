@@ -16,6 +16,8 @@
 // Six builds, all 8 wavefronts x 16 rows: 1, 2, 3, 4, 6 or 8 tiles of 16 rows of H (M <= 16, 32,
 // 48, 64, 96, 128), with H chunks of 512, 512, 512, 256, 256 and 128 elements; bound by HBM up to about 100 rows of
 // H, by the matrix cores and the LDS reads of the H fragments beyond.
+#include <type_traits>
+
 #include "epilogue.hpp"
 #include "internal.hpp"
 
@@ -358,12 +360,17 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
                 const FoldSink out{!last ? FoldTo::kLds : (a.mailbox ? FoldTo::kMailbox : FoldTo::kPartials),
                                    a.part, a.mail, (int)blockIdx.x, run_ms, run_val, run_id};
                 constexpr bool kQuad = Mp > 2 * WAVES;   // two rows per wavefront would take several rounds
-                if (p == (int)blockIdx.x)
-                    fold_pass<kZR, false, false, kQuad>(z_all, kZR + kZPad, 1, 0, ids_lds, n_valid, a.k, 0, a.M, wave,
-                                                        WAVES, row_of, out, &s_select[wave]);
-                else
-                    fold_pass<kZR, true, false, kQuad>(z_all, kZR + kZPad, 1, 0, ids_lds, n_valid, a.k, 0, a.M, wave,
-                                                       WAVES, row_of, out, &s_select[wave]);
+                auto fold_with = [&](auto b32) {   // (bound from 16 groups up to k = 10, from 32 beyond)
+                    constexpr bool B32 = decltype(b32)::value;
+                    if (p == (int)blockIdx.x)
+                        fold_pass<kZR, false, false, kQuad, B32>(z_all, kZR + kZPad, 1, 0, ids_lds, n_valid, a.k, 0, a.M,
+                                                                 wave, WAVES, row_of, out, &s_select[wave]);
+                    else
+                        fold_pass<kZR, true, false, kQuad, B32>(z_all, kZR + kZPad, 1, 0, ids_lds, n_valid, a.k, 0, a.M,
+                                                                wave, WAVES, row_of, out, &s_select[wave]);
+                };
+                if (a.k >= kBound32FromK) fold_with(std::true_type{});
+                else fold_with(std::false_type{});
             }
         }
     }
@@ -385,8 +392,13 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
             const int R = G < a.M ? G : a.M;
             if (gidx < G - R) return;
             stamp(4);
-            merge_rows_mailbox<(WAVES >= 8 ? 8 : 4)>(mb, part, a.ticket + 1, G, gidx - (G - R), R, a.M, a.k, a.token_ids, a.logp,
-                               &s_merge, &s_select[0], nullptr, a.spin_limit ? a.spin_limit : kMailSpinLimit);
+            const unsigned spin = a.spin_limit ? a.spin_limit : kMailSpinLimit;
+            if (a.k >= kBound32FromK)
+                merge_rows_mailbox<(WAVES >= 8 ? 8 : 4), true>(mb, part, a.ticket + 1, G, gidx - (G - R), R, a.M, a.k,
+                                                               a.token_ids, a.logp, &s_merge, &s_select[0], nullptr, spin);
+            else
+                merge_rows_mailbox<(WAVES >= 8 ? 8 : 4), false>(mb, part, a.ticket + 1, G, gidx - (G - R), R, a.M, a.k,
+                                                                a.token_ids, a.logp, &s_merge, &s_select[0], nullptr, spin);
             __syncthreads();
             stamp(5);
         }

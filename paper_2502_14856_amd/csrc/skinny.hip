@@ -22,6 +22,8 @@
 //     and write the outputs (for k <= 16 through self-validating mailbox records).
 // For small vocabularies several wavefronts share a tile and split d between them
 // (KS > 1) so that every compute unit still has enough loads in flight.
+#include <type_traits>
+
 #include "epilogue.hpp"
 #include "internal.hpp"
 
@@ -107,7 +109,9 @@ struct SkinnyLds {
  * wavefront's pace is set by the latency of its die's memory path, not by its own byte
  * count, so it does not matter which wavefront of a die carries fewer or more rows.)
  */
-template <int MT, int WAVES, int DEPTH, bool MFMA, bool TILED = false, bool SKEW = false, int HR = 16>
+// B32: the bound of the folds and of the merge from 32 groups (the build for k = 11 .. 16).  A build of
+// its own: both instances of that code in one kernel cost the k <= 10 calls 0.3 us.
+template <int MT, int WAVES, int DEPTH, bool MFMA, bool TILED = false, bool SKEW = false, int HR = 16, bool B32 = false>
 __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     static_assert(MFMA || !TILED, "the tiled layout is the matrix cores' operand order");
     static_assert(!SKEW || (MFMA && !TILED), "the skewed build is the default build plus one wavefront");
@@ -482,10 +486,10 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
                 // logits per lane of the one laid out for 128 (of which half the lanes would hold none)
                 if (KS == 2) {
                     if (p == first_pass)
-                        fold_pass<ZR_MAX / 2, false, false, false>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, 0, a.M,
+                        fold_pass<ZR_MAX / 2, false, false, false, B32>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, 0, a.M,
                                                                    wave, FOLD_WAVES, row_of, out, &s_select[wave]);
                     else
-                        fold_pass<ZR_MAX / 2, true, false, false>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, 0, a.M,
+                        fold_pass<ZR_MAX / 2, true, false, false, B32>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, 0, a.M,
                                                                   wave, FOLD_WAVES, row_of, out, &s_select[wave]);
                     folded = true;
                 }
@@ -493,10 +497,10 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
             if (folded || (SKEW && wave >= FOLD_WAVES)) {
                 // (done; or the ninth wavefront, which only streams)
             } else if (p == first_pass) {
-                fold_pass<ZR_MAX, false, SKEW, kQuadFold>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, 0, a.M, wave,
+                fold_pass<ZR_MAX, false, SKEW, kQuadFold, B32>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, 0, a.M, wave,
                                                FOLD_WAVES, row_of, out, &s_select[wave]);
             } else {
-                fold_pass<ZR_MAX, true, SKEW, kQuadFold>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, 0, a.M, wave,
+                fold_pass<ZR_MAX, true, SKEW, kQuadFold, B32>(z_lds, ZR, KS, MT * ZR, ids_lds, n_valid, a.k, 0, a.M, wave,
                                               FOLD_WAVES, row_of, out, &s_select[wave]);
             }
         }
@@ -530,8 +534,8 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
         if (b > top || b % spread != 0 || r >= R) return;
         stamp(4);
         const unsigned spin = a.spin_limit ? a.spin_limit : kMailSpinLimit;
-        merge_rows_mailbox<(WAVES >= 8 ? 8 : 4)>(a.mail, part, a.ticket + 1, G, r, R, a.M, a.k, a.token_ids, a.logp, &s_merge,
-                           &s_select[0], a.step.rec, spin);
+        merge_rows_mailbox<(WAVES >= 8 ? 8 : 4), B32>(a.mail, part, a.ticket + 1, G, r, R, a.M, a.k, a.token_ids, a.logp, &s_merge,
+                                                      &s_select[0], a.step.rec, spin);
         // the first merger also runs the beam-search expansion of the step, if one was asked for
         if (a.step.rec && r == 0 && wave == 0)
             expand_step_fused(a.step, a.M, a.k, reinterpret_cast<unsigned long long *>(s_select), a.ticket + 1, spin);
@@ -611,7 +615,15 @@ constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 constexpr int kMfmaTile = 16;   // the matrix-core variant is compiled once, for up to 16 rows
 
 // The kernel build behind a variant, for M rows of H (MT: width of the vector-ALU tile).
-SkinnyKernel select_kernel(int variant, int M, int MT) {
+SkinnyKernel select_kernel(int variant, int M, int MT, bool b32 = false) {
+    if (variant == 0 && b32) {   // the default build for k = 11 .. 16
+        if (M <= 2) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 2, true>;
+        if (M <= 4) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 4, true>;
+        if (M <= 8) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 8, true>;
+        if (M <= 10) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 10, true>;
+        if (M <= 12) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 12, true>;
+        return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 16, true>;
+    }
     switch (variant) {
         case 0:
             // the default build exists once per number of H rows it requests at its start
@@ -661,12 +673,15 @@ int default_variant(int M, int d, int k, bool vector_alu, bool tiled) {
 fr_status prepare_skinny_kernels() {
     for (int variant = 0; variant < kNumVariants; ++variant)
         for (int M = 1; M <= kSkinnyMaxM; ++M) {
-            const SkinnyKernel kern = select_kernel(variant, M, kVariants[variant].mfma ? kMfmaTile : bucket_for(M));
-            if (!kern) return FR_ERR_HIP;
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    kLdsBudget - kStaticLdsReserve) != hipSuccess) {
-                (void)hipGetLastError();
-                return FR_ERR_HIP;
+            for (int b32 = 0; b32 < 2; ++b32) {
+                const SkinnyKernel kern =
+                    select_kernel(variant, M, kVariants[variant].mfma ? kMfmaTile : bucket_for(M), b32 != 0);
+                if (!kern) return FR_ERR_HIP;
+                if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        kLdsBudget - kStaticLdsReserve) != hipSuccess) {
+                    (void)hipGetLastError();
+                    return FR_ERR_HIP;
+                }
             }
         }
     return FR_OK;
@@ -783,7 +798,7 @@ fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hip
     }
     const int lds = lds_bytes(p.M, p.d, p.k, variant);
 
-    const SkinnyKernel kern = select_kernel(variant, a.M, MT);
+    const SkinnyKernel kern = select_kernel(variant, a.M, MT, p.k >= kBound32FromK && p.k <= kSmallKMax);
     if (!kern) return FR_ERR_INVALID_ARG;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kVariants[variant].waves * kWave), lds, s, a);
     const fr_status st = hip_status(hipGetLastError());

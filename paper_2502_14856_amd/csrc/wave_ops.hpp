@@ -157,6 +157,43 @@ __device__ __forceinline__ unsigned row16_kth_largest_u32(unsigned v, int k) {
     return row16_min_u32(greater < k ? v : 0xFFFFFFFFu);
 }
 
+// The same over the 32 values held by the lanes of each half of the wavefront (two DPP rows):
+// a lane counts the larger ones in its own row by rotations, and in the other row of its half
+// by rotations of the value it receives from there (lane-swap instruction, no LDS pipe).
+template <int N>
+__device__ __forceinline__ int row16_count_greater_than(unsigned w, unsigned v) {
+    int c = (unsigned)dpp_i32<0x120 + N>((int)w) > v;   // row_ror:N
+    if constexpr (N > 1) c += row16_count_greater_than<N - 1>(w, v);
+    return c;
+}
+__device__ __forceinline__ unsigned half32_kth_largest_u32(unsigned v, int k) {
+    const auto sw = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    const unsigned other = (unsigned)sw[0] == v ? (unsigned)sw[1] : (unsigned)sw[0];   // v[l ^ 16]
+    const int greater = row16_count_greater<15>(v) + (other > v) + row16_count_greater_than<15>(other, v);
+    const unsigned cand = row16_min_u32(greater < k ? v : 0xFFFFFFFFu);
+    const auto sm = __builtin_amdgcn_permlane16_swap(cand, cand, false, false);
+    return min((unsigned)sm[0], (unsigned)sm[1]);
+}
+// ... and over the 32 values that the 16 lanes of a DPP row hold two at a time (a, b).
+template <int N>
+__device__ __forceinline__ void row16_count_greater_pair(unsigned a, unsigned b, int &ga, int &gb) {
+    const unsigned ra = (unsigned)dpp_i32<0x120 + N>((int)a), rb = (unsigned)dpp_i32<0x120 + N>((int)b);
+    ga += (ra > a) + (rb > a);
+    gb += (ra > b) + (rb > b);
+    if constexpr (N > 1) row16_count_greater_pair<N - 1>(a, b, ga, gb);
+}
+__device__ __forceinline__ unsigned row16x2_kth_largest_u32(unsigned a, unsigned b, int k) {
+    int ga = b > a, gb = a > b;
+    row16_count_greater_pair<15>(a, b, ga, gb);
+    return row16_min_u32(min(ga < k ? a : 0xFFFFFFFFu, gb < k ? b : 0xFFFFFFFFu));
+}
+// From this k on a bound from 16 group maxima admits too much (at k = 16 it is the smallest of them):
+// the folds and the merge that have 32 values at hand take the k-th largest of 32 groups instead.
+// The choice is a template argument of the folds and of the merge (B32), made once per pass by the
+// kernels: as a run-time choice inside them it cost the k <= 10 calls 0.3 us (the compiler computes
+// both bounds and selects, or, with the 32-group bound out of line, keeps registers clear for the call).
+constexpr int kBound32FromK = 11;
+
 // (value, id) ordering of the candidate lists: larger value first, equal values by
 // lower token id.
 __device__ __forceinline__ bool cand_before(float va, int ida, float vb, int idb) {

@@ -150,7 +150,11 @@ def test_tiny_config_draft_topk():
 @pytest.mark.parametrize("M,d,V,V_sub,k", [
     (1, 256, 4096, 1024, 1), (10, 512, 6000, 3000, 10), (16, 256, 5000, 2500, 16),
     (5, 264, 3000, 777, 7), (10, 1024, 9000, 4099, 33), (3, 128, 2000, 1999, 64),
-    (2, 64, 100, 10, 10), (10, 4096, 2000, 640, 10), (4, 8192, 3000, 1500, 8)])
+    (2, 64, 100, 10, 10), (10, 4096, 2000, 640, 10), (4, 8192, 3000, 1500, 8),
+    # k = 11 .. 16: the bound of the folds and of the merge comes from 32 groups instead of 16
+    (10, 512, 40000, 36000, 11), (10, 256, 70000, 66000, 12), (7, 512, 40000, 20000, 13),
+    (12, 256, 40000, 33000, 14), (10, 512, 50000, 40960, 15), (16, 256, 70000, 65536, 16),
+    (10, 128, 3000, 16, 16), (3, 256, 5000, 300, 15)])
 def test_draft_topk_skinny(M, d, V, V_sub, k):
     _say("draft skinny", M, d, V, V_sub, k)
     W, H, r = _case(V, d, M, 5)
