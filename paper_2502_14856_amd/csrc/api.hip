@@ -172,6 +172,16 @@ fr_status head_topk(const void *H, int64_t M, int64_t d, const void *W, const in
         const bool skinny_only = row_delta || step;
         path = (M <= kSkinnyMaxM && (skinny_only ? skinny_fits((int)M, (int)d, k)
                                                  : skinny_fits_eight_waves((int)M, (int)d, k))) ? 3 : 2;
+        // Rows of H longer than 8 KiB: the skinny kernel's 512 threads request one 16-byte column of H
+        // each ahead of W and fetch the columns beyond that later, behind the first batch of W; the
+        // chunked kernel stages H in pieces anyway and is 1 to 4 us faster there from two rows of H
+        // on (measured at d = 4608, 5120, 6144; at 8192 the two are level), as long as there is a 128-row
+        // pass for every compute unit (with fewer rows of W only the skinny kernel splits d between its
+        // wavefronts).
+        if (path == 3 && !skinny_only && d > 4096 && d < 8192 && M >= 2 && k <= kMailK) {
+            const int cus = device_cu_count();
+            if (cus > 0 && V_rows >= static_cast<int64_t>(128) * cus) path = 2;
+        }
     }
     if ((row_delta || step) && path == 2) return FR_ERR_UNSUPPORTED;
     const bool two_launch = tuning && tuning->two_launch;
