@@ -182,6 +182,14 @@ fr_status head_topk(const void *H, int64_t M, int64_t d, const void *W, const in
             const int cus = device_cu_count();
             if (cus > 0 && V_rows >= static_cast<int64_t>(128) * cus) path = 2;
         }
+        // The other way round on small subsets: the chunked kernel works in passes of 128 rows, so
+        // with few rows of W per compute unit most of the device idles; the skinny kernel's
+        // four-wavefront build, which splits d, then wins where it holds H (22.5 against 30.2 us at
+        // 8192 rows, 13 rows of H; at 16384 rows, 64 per compute unit, it loses: 38 against 32 us).
+        if (path == 2 && M <= kSkinnyMaxM && skinny_fits((int)M, (int)d, k)) {
+            const int cus = device_cu_count();
+            if (cus > 0 && V_rows <= static_cast<int64_t>(48) * cus) path = 3;
+        }
     }
     if ((row_delta || step) && path == 2) return FR_ERR_UNSUPPORTED;
     const bool two_launch = tuning && tuning->two_launch;
