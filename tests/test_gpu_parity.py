@@ -154,7 +154,10 @@ def test_tiny_config_draft_topk():
     # k = 11 .. 16: the bound of the folds and of the merge comes from 32 groups instead of 16
     (10, 512, 40000, 36000, 11), (10, 256, 70000, 66000, 12), (7, 512, 40000, 20000, 13),
     (12, 256, 40000, 33000, 14), (10, 512, 50000, 40960, 15), (16, 256, 70000, 65536, 16),
-    (10, 128, 3000, 16, 16), (3, 256, 5000, 300, 15)])
+    (10, 128, 3000, 16, 16), (3, 256, 5000, 300, 15),
+    # the two routing rules that depend on the rows of W per compute unit: long rows of H with a pass for
+    # every compute unit (chunked kernel), 13 / 14 rows of H on a small subset (four-wavefront skinny build)
+    (4, 5120, 33000, 32768, 10), (13, 4096, 9000, 8192, 10), (14, 2048, 14000, 12288, 7)])
 def test_draft_topk_skinny(M, d, V, V_sub, k):
     _say("draft skinny", M, d, V, V_sub, k)
     W, H, r = _case(V, d, M, 5)
