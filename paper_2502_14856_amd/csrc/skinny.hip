@@ -111,7 +111,13 @@ struct SkinnyLds {
  */
 // B32: the bound of the folds and of the merge from 32 groups (the build for k = 11 .. 16).  A build of
 // its own: both instances of that code in one kernel cost the k <= 10 calls 0.3 us.
-template <int MT, int WAVES, int DEPTH, bool MFMA, bool TILED = false, bool SKEW = false, int HR = 16, bool B32 = false>
+// LEAN: the build for the plain fused call (single launch through the mailbox, no fused beam-search step,
+// no phase trace, default wait limit): those choices are compile-time constants in it, which frees
+// registers (212 against 220 vector registers, 162 against 217 scalar spills) and is worth 0.55 us per
+// call at every size.  (Fixing the wavefronts per tile along d, or M and k, at compile time as well
+// measured no further gain.)
+template <int MT, int WAVES, int DEPTH, bool MFMA, bool TILED = false, bool SKEW = false, int HR = 16, bool B32 = false,
+          bool LEAN = false>
 __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     static_assert(MFMA || !TILED, "the tiled layout is the matrix cores' operand order");
     static_assert(!SKEW || (MFMA && !TILED), "the skewed build is the default build plus one wavefront");
@@ -196,14 +202,16 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     }
     const bool has_tile = !SKEW || tile_in_pass * kTileRows < blk_rows;   // wave-uniform
     auto stamp = [&](int slot) {
-        if (a.trace && tid == 0) a.trace[blockIdx.x * 8 + slot] = (long long)__builtin_amdgcn_s_memrealtime();
+        if constexpr (!LEAN)
+            if (a.trace && tid == 0) a.trace[blockIdx.x * 8 + slot] = (long long)__builtin_amdgcn_s_memrealtime();
     };
+    const int sink = LEAN ? (int)Sink::kFusedTopk : a.sink;
     stamp(0);
     // which arrival counter this call uses: asked for now, needed at the very end
     const Arrival ar(a.ticket);
     // single launch, k <= 16, at most 256 workgroups: results travel as mailbox records
-    const bool mailbox = a.sink == (int)Sink::kFusedTopk && a.k <= kSmallKMax && G <= 4 * kWave;
-    const unsigned turn = (a.sink == (int)Sink::kFusedTopk && !mailbox) ? ar.turn() : 0u;
+    const bool mailbox = LEAN || (sink == (int)Sink::kFusedTopk && a.k <= kSmallKMax && G <= 4 * kWave);
+    const unsigned turn = (sink == (int)Sink::kFusedTopk && !mailbox) ? ar.turn() : 0u;
 
     // Step range of this wavefront along d, split into a pipelined part (whole groups of
     // DEPTH full steps, no bounds handling at all) and leftovers (at most DEPTH - 1 steps,
@@ -463,7 +471,7 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
         stamp(2);
 
         // ---- consume the pass ----
-        if (a.sink == (int)Sink::kLogits) {
+        if (sink == (int)Sink::kLogits) {
             for (int i = tid; i < a.M * ZR; i += WAVES * kWave) {
                 const int m = i / ZR, r = i - m * ZR;
                 if (r < n_valid) {
@@ -472,7 +480,7 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
                     a.z_out[(size_t)m * a.z_ld + pass_row0 + r] = z;
                 }
             }
-        } else if (a.sink != (int)Sink::kStreamOnly) {
+        } else if (sink != (int)Sink::kStreamOnly) {
             auto row_of = [&](int m) {
                 return FoldRow{z_lds + m * ZR, run_ms + 2 * m, run_val + m * a.k, run_id + m * a.k};
             };
@@ -514,9 +522,9 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
         }
     }
 
-    if (a.sink == (int)Sink::kLogits || a.sink == (int)Sink::kStreamOnly) return;
+    if (sink == (int)Sink::kLogits || sink == (int)Sink::kStreamOnly) return;
     stamp(3);
-    if (a.sink == (int)Sink::kPartialsOnly) return;
+    if (sink == (int)Sink::kPartialsOnly) return;
 
     // ---- some of the workgroups merge all partials (single launch) ----
     const int R = merger_count(G, a.M);
@@ -533,11 +541,12 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
         const int r = (top - b) / spread;
         if (b > top || b % spread != 0 || r >= R) return;
         stamp(4);
-        const unsigned spin = a.spin_limit ? a.spin_limit : kMailSpinLimit;
+        const unsigned spin = LEAN ? kMailSpinLimit : (a.spin_limit ? a.spin_limit : kMailSpinLimit);
+        unsigned long long *const step_rec = LEAN ? nullptr : a.step.rec;
         merge_rows_mailbox<(WAVES >= 8 ? 8 : 4), B32>(a.mail, part, a.ticket + 1, G, r, R, a.M, a.k, a.token_ids, a.logp, &s_merge,
-                                                      &s_select[0], a.step.rec, spin);
+                                                      &s_select[0], step_rec, spin);
         // the first merger also runs the beam-search expansion of the step, if one was asked for
-        if (a.step.rec && r == 0 && wave == 0)
+        if (step_rec && r == 0 && wave == 0)
             expand_step_fused(a.step, a.M, a.k, reinterpret_cast<unsigned long long *>(s_select), a.ticket + 1, spin);
     } else {
         const int r = arrive_and_wait(ar, (unsigned)__builtin_amdgcn_readfirstlane((int)turn), G, R, &s_slot,
@@ -615,7 +624,23 @@ constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 constexpr int kMfmaTile = 16;   // the matrix-core variant is compiled once, for up to 16 rows
 
 // The kernel build behind a variant, for M rows of H (MT: width of the vector-ALU tile).
-SkinnyKernel select_kernel(int variant, int M, int MT, bool b32 = false) {
+SkinnyKernel select_kernel(int variant, int M, int MT, bool b32 = false, bool lean = false) {
+    if (variant == 0 && lean) {   // the default build for the plain fused call: k <= 10, and k = 11 .. 16
+        if (b32) {
+            if (M <= 2) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 2, true, true>;
+            if (M <= 4) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 4, true, true>;
+            if (M <= 8) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 8, true, true>;
+            if (M <= 10) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 10, true, true>;
+            if (M <= 12) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 12, true, true>;
+            return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 16, true, true>;
+        }
+        if (M <= 2) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 2, false, true>;
+        if (M <= 4) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 4, false, true>;
+        if (M <= 8) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 8, false, true>;
+        if (M <= 10) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 10, false, true>;
+        if (M <= 12) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 12, false, true>;
+        return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 16, false, true>;
+    }
     if (variant == 0 && b32) {   // the default build for k = 11 .. 16
         if (M <= 2) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 2, true>;
         if (M <= 4) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 4, true>;
@@ -673,9 +698,9 @@ int default_variant(int M, int d, int k, bool vector_alu, bool tiled) {
 fr_status prepare_skinny_kernels() {
     for (int variant = 0; variant < kNumVariants; ++variant)
         for (int M = 1; M <= kSkinnyMaxM; ++M) {
-            for (int b32 = 0; b32 < 2; ++b32) {
-                const SkinnyKernel kern =
-                    select_kernel(variant, M, kVariants[variant].mfma ? kMfmaTile : bucket_for(M), b32 != 0);
+            for (int build = 0; build < 4; ++build) {   // 16 / 32 groups of the bound x general / lean
+                const SkinnyKernel kern = select_kernel(variant, M, kVariants[variant].mfma ? kMfmaTile : bucket_for(M),
+                                                        (build & 1) != 0, (build & 2) != 0);
                 if (!kern) return FR_ERR_HIP;
                 if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                         kLdsBudget - kStaticLdsReserve) != hipSuccess) {
@@ -798,7 +823,9 @@ fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hip
     }
     const int lds = lds_bytes(p.M, p.d, p.k, variant);
 
-    const SkinnyKernel kern = select_kernel(variant, a.M, MT, p.k >= kBound32FromK && p.k <= kSmallKMax);
+    const bool lean = sink == Sink::kFusedTopk && p.k <= kSmallKMax && grid <= 4 * kWave && !a.step.rec && !a.trace &&
+                      a.spin_limit == 0u;
+    const SkinnyKernel kern = select_kernel(variant, a.M, MT, p.k >= kBound32FromK && p.k <= kSmallKMax, lean);
     if (!kern) return FR_ERR_INVALID_ARG;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kVariants[variant].waves * kWave), lds, s, a);
     const fr_status st = hip_status(hipGetLastError());
