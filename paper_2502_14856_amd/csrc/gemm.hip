@@ -95,7 +95,9 @@ struct BlockLds {
 // position of chunk c of row `row` inside a stage (16-byte units)
 __host__ __device__ constexpr int swizzled(int row, int c) { return row * kStepChunks + (c ^ ((row >> 1) & 7)); }
 
-template <int NT>
+// LEAN: the build for the plain fused call (sink, mailbox, no trace as compile-time constants), as in
+// the skinny kernel.
+template <int NT, bool LEAN = false>
 __global__ __launch_bounds__(kBlockThreads) void block_kernel(BlockArgs a) {
     constexpr int Mp = 64 * NT;
     constexpr int kHStage16 = Mp * kStepChunks;                 // 16-byte units per H buffer
@@ -129,11 +131,15 @@ __global__ __launch_bounds__(kBlockThreads) void block_kernel(BlockArgs a) {
     const int lt = tid & (kRoleThreads - 1);   // thread number inside its loading role
     const int G = gridDim.x;
     auto stamp = [&](int slot) {
-        if (a.trace && tid == 0) a.trace[blockIdx.x * 8 + slot] = (long long)__builtin_amdgcn_s_memrealtime();
+        if constexpr (!LEAN)
+            if (a.trace && tid == 0) a.trace[blockIdx.x * 8 + slot] = (long long)__builtin_amdgcn_s_memrealtime();
     };
     stamp(0);
+    // (lean build: the plain fused call through the mailbox, no phase trace, default wait limit)
+    const int sink = LEAN ? (int)Sink::kFusedTopk : a.sink;
+    const bool mailbox = LEAN || a.mailbox != 0;
     const Arrival ar(a.ticket);
-    const unsigned turn = a.sink == (int)Sink::kFusedTopk ? ar.turn() : 0u;
+    const unsigned turn = (!LEAN && sink == (int)Sink::kFusedTopk) ? ar.turn() : 0u;
 
     for (int i = tid; i < Mp * a.k; i += kBlockThreads) {
         run_val[i] = kNegInf;
@@ -334,18 +340,18 @@ __global__ __launch_bounds__(kBlockThreads) void block_kernel(BlockArgs a) {
             }
             __syncthreads();
             const int m_end = min(a.M, m_base + kFoldRows);
-            if (a.sink == (int)Sink::kLogits) {
+            if (sink == (int)Sink::kLogits) {
                 for (int e = tid; e < kFoldRows * kTV; e += kBlockThreads) {
                     const int m = m_base + e / kTV, r = e % kTV;
                     if (m < m_end && r < n_valid)
                         a.z_out[(size_t)m * a.z_ld + pass_row0 + r] = z_all[(m - m_base) * (kTV + kZPad) + r];
                 }
-            } else if (a.sink != (int)Sink::kStreamOnly) {
+            } else if (sink != (int)Sink::kStreamOnly) {
                 auto row_of = [&](int m) {
                     return FoldRow{z_all + (m - m_base) * (kTV + kZPad), run_ms + 2 * m, run_val + m * a.k,
                                    run_id + m * a.k};
                 };
-                const FoldSink out{!last ? FoldTo::kLds : (a.mailbox ? FoldTo::kMailbox : FoldTo::kPartials),
+                const FoldSink out{!last ? FoldTo::kLds : (mailbox ? FoldTo::kMailbox : FoldTo::kPartials),
                                    a.part, a.mail, (int)blockIdx.x, run_ms, run_val, run_id};
                 auto fold_with = [&](auto b32) {   // (bound from 16 groups up to k = 10, from 32 beyond)
                     constexpr bool B32 = decltype(b32)::value;
@@ -362,17 +368,17 @@ __global__ __launch_bounds__(kBlockThreads) void block_kernel(BlockArgs a) {
         }
     }
 
-    if (a.sink == (int)Sink::kLogits || a.sink == (int)Sink::kStreamOnly) return;
+    if (sink == (int)Sink::kLogits || sink == (int)Sink::kStreamOnly) return;
     stamp(3);
     const int gidx = blockIdx.x;
     const Partials part = a.part;
-    if (a.mailbox) {
+    if (mailbox) {
         // as in the chunked kernel: the last R workgroups of the grid merge one row of H each
         const Mailbox mb = a.mail;
         const int R = G < a.M ? G : a.M;
         if (gidx < G - R) return;
         stamp(4);
-        const unsigned spin = a.spin_limit ? a.spin_limit : kMailSpinLimit;
+        const unsigned spin = LEAN ? kMailSpinLimit : (a.spin_limit ? a.spin_limit : kMailSpinLimit);
         if (a.k >= kBound32FromK)
             merge_rows_mailbox<8, true>(mb, part, a.ticket + 1, G, gidx - (G - R), R, a.M, a.k, a.token_ids, a.logp,
                                         &s_merge, &s_select[0], nullptr, spin);
@@ -383,7 +389,7 @@ __global__ __launch_bounds__(kBlockThreads) void block_kernel(BlockArgs a) {
         stamp(5);
         return;
     }
-    if (a.sink == (int)Sink::kPartialsOnly) return;
+    if (sink == (int)Sink::kPartialsOnly) return;
 
     const int R = merger_count(G, a.M);
     const int r = arrive_and_wait(ar, (unsigned)__builtin_amdgcn_readfirstlane((int)turn), G, R, &s_slot,
@@ -399,11 +405,11 @@ constexpr int kLdsBudget = 160 * 1024;
 constexpr int kStaticLdsReserve = 12 * 1024;
 
 typedef void (*BlockKernel)(BlockArgs);
-BlockKernel select_kernel(int nt) {
+BlockKernel select_kernel(int nt, bool lean = false) {
     switch (nt) {
-        case 2: return block_kernel<2>;
-        case 3: return block_kernel<3>;
-        case 4: return block_kernel<4>;
+        case 2: return lean ? block_kernel<2, true> : block_kernel<2>;
+        case 3: return lean ? block_kernel<3, true> : block_kernel<3>;
+        case 4: return lean ? block_kernel<4, true> : block_kernel<4>;
     }
     return nullptr;
 }
@@ -412,8 +418,8 @@ int tiles_for(int M) { return M <= 128 ? 2 : M <= 192 ? 3 : 4; }
 }  // namespace
 
 fr_status prepare_block_kernels() {
-    for (int nt = 2; nt <= 4; ++nt)
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(select_kernel(nt)),
+    for (int b = 0; b < 6; ++b)
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(select_kernel(2 + b / 2, (b & 1) != 0)),
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                 kLdsBudget - kStaticLdsReserve) != hipSuccess) {
             (void)hipGetLastError();
@@ -465,7 +471,8 @@ fr_status launch_block(const HeadProblem &p, Sink sink, const fr_tuning *t, hipS
     a.mailbox = sink == Sink::kFusedTopk && p.k <= kMailK && p.M <= kMailRows && grid <= 4 * kWave &&
                 !(t && t->no_mailbox);
 
-    hipLaunchKernelGGL(select_kernel(nt), dim3(grid), dim3(kBlockThreads), lds, s, a);
+    const bool lean = sink == Sink::kFusedTopk && a.mailbox && !a.trace && a.spin_limit == 0u;
+    hipLaunchKernelGGL(select_kernel(nt, lean), dim3(grid), dim3(kBlockThreads), lds, s, a);
     const fr_status st = hip_status(hipGetLastError());
     if (st != FR_OK) return st;
     if (sink == Sink::kPartialsOnly) return launch_merge(p, grid, s);

@@ -74,7 +74,9 @@ struct WideLds {
     }
 };
 
-template <int MT16, int RB, int WAVES, int DEPTH, int HCH>
+// LEAN: the build for the plain fused call (sink, mailbox, no trace as compile-time constants), as in
+// the skinny kernel.
+template <int MT16, int RB, int WAVES, int DEPTH, int HCH, bool LEAN = false>
 __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
     static_assert(WAVES * RB * 16 == kZR, "a pass is 128 vocabulary rows");
     static_assert((2 * DEPTH) % HCH == 0, "groups of steps start on an H chunk boundary");
@@ -104,12 +106,16 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
     const int j = lk, g = rs;                   // operand layout: row / column, k group
     const int G = gridDim.x;
     auto stamp = [&](int slot) {
-        if (a.trace && tid == 0) a.trace[blockIdx.x * 8 + slot] = (long long)__builtin_amdgcn_s_memrealtime();
+        if constexpr (!LEAN)
+            if (a.trace && tid == 0) a.trace[blockIdx.x * 8 + slot] = (long long)__builtin_amdgcn_s_memrealtime();
     };
     stamp(0);
     // which arrival counter this call uses: asked for now, needed at the very end
+    // (lean build: the plain fused call through the mailbox, no phase trace, default wait limit)
+    const int sink = LEAN ? (int)Sink::kFusedTopk : a.sink;
+    const bool mailbox = LEAN || a.mailbox != 0;
     const Arrival ar(a.ticket);
-    const unsigned turn = a.sink == (int)Sink::kFusedTopk ? ar.turn() : 0u;
+    const unsigned turn = (!LEAN && sink == (int)Sink::kFusedTopk) ? ar.turn() : 0u;
 
     for (int i = tid; i < Mp * a.k; i += NT) {
         run_val[i] = kNegInf;
@@ -345,19 +351,19 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
                     *reinterpret_cast<f32x4_t *>(dst) = acc[rb][mt];
                 }
             __syncthreads();
-            if (a.sink == (int)Sink::kLogits) {
+            if (sink == (int)Sink::kLogits) {
                 for (int e = tid; e < Mp * kZR; e += NT) {
                     const int m = e / kZR, r = e - m * kZR;
                     if (m < a.M && r < n_valid)
                         a.z_out[(size_t)m * a.z_ld + pass_row0 + r] = z_all[m * (kZR + kZPad) + r];
                 }
-            } else if (a.sink != (int)Sink::kStreamOnly) {
+            } else if (sink != (int)Sink::kStreamOnly) {
                 auto row_of = [&](int m) {
                     return FoldRow{z_all + m * (kZR + kZPad), run_ms + 2 * m, run_val + m * a.k, run_id + m * a.k};
                 };
                 // the last pass of the workgroup writes its result out instead of keeping it
                 const bool last = p + G >= a.passes;
-                const FoldSink out{!last ? FoldTo::kLds : (a.mailbox ? FoldTo::kMailbox : FoldTo::kPartials),
+                const FoldSink out{!last ? FoldTo::kLds : (mailbox ? FoldTo::kMailbox : FoldTo::kPartials),
                                    a.part, a.mail, (int)blockIdx.x, run_ms, run_val, run_id};
                 constexpr bool kQuad = Mp > 2 * WAVES;   // two rows per wavefront would take several rounds
                 auto fold_with = [&](auto b32) {   // (bound from 16 groups up to k = 10, from 32 beyond)
@@ -375,13 +381,13 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
         }
     }
 
-    if (a.sink == (int)Sink::kLogits || a.sink == (int)Sink::kStreamOnly) return;
+    if (sink == (int)Sink::kLogits || sink == (int)Sink::kStreamOnly) return;
 
     // (every workgroup's last fold has written its lists and statistics out)
     stamp(3);
     const int gidx = blockIdx.x;
     const Partials part = a.part;   // a local copy keeps the argument block itself in registers
-    if (a.mailbox) {
+    if (mailbox) {
         // The results are self-validating records; the mergers (one per row of H while there
         // are enough workgroups) poll for them: nothing to count.  The mergers are the LAST
         // workgroups of the grid: workgroups start in order, so once the R <= 128 mergers are on
@@ -392,7 +398,7 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
             const int R = G < a.M ? G : a.M;
             if (gidx < G - R) return;
             stamp(4);
-            const unsigned spin = a.spin_limit ? a.spin_limit : kMailSpinLimit;
+            const unsigned spin = LEAN ? kMailSpinLimit : (a.spin_limit ? a.spin_limit : kMailSpinLimit);
             if (a.k >= kBound32FromK)
                 merge_rows_mailbox<(WAVES >= 8 ? 8 : 4), true>(mb, part, a.ticket + 1, G, gidx - (G - R), R, a.M, a.k,
                                                                a.token_ids, a.logp, &s_merge, &s_select[0], nullptr, spin);
@@ -404,7 +410,7 @@ __global__ __launch_bounds__(WAVES * kWave) void wide_kernel(WideArgs a) {
         }
         return;
     }
-    if (a.sink == (int)Sink::kPartialsOnly) return;
+    if (sink == (int)Sink::kPartialsOnly) return;
 
     const int R = merger_count(G, a.M);
     const int r = arrive_and_wait(ar, (unsigned)__builtin_amdgcn_readfirstlane((int)turn), G, R, &s_slot,
@@ -437,14 +443,14 @@ typedef void (*WideKernel)(WideArgs);
 constexpr int kWideWaves = 8;
 
 // the build for `mt16` tiles of 16 rows of H
-WideKernel select_kernel(int mt16) {
+WideKernel select_kernel(int mt16, bool lean = false) {
     switch (mt16) {
-        case 1: return wide_kernel<1, 1, kWideWaves, 4, 8>;
-        case 2: return wide_kernel<2, 1, kWideWaves, 4, 8>;
-        case 3: return wide_kernel<3, 1, kWideWaves, 4, 8>;
-        case 4: return wide_kernel<4, 1, kWideWaves, 4, 4>;
-        case 6: return wide_kernel<6, 1, kWideWaves, 4, 4>;
-        case 8: return wide_kernel<8, 1, kWideWaves, 4, 2>;
+        case 1: return lean ? wide_kernel<1, 1, kWideWaves, 4, 8, true> : wide_kernel<1, 1, kWideWaves, 4, 8>;
+        case 2: return lean ? wide_kernel<2, 1, kWideWaves, 4, 8, true> : wide_kernel<2, 1, kWideWaves, 4, 8>;
+        case 3: return lean ? wide_kernel<3, 1, kWideWaves, 4, 8, true> : wide_kernel<3, 1, kWideWaves, 4, 8>;
+        case 4: return lean ? wide_kernel<4, 1, kWideWaves, 4, 4, true> : wide_kernel<4, 1, kWideWaves, 4, 4>;
+        case 6: return lean ? wide_kernel<6, 1, kWideWaves, 4, 4, true> : wide_kernel<6, 1, kWideWaves, 4, 4>;
+        case 8: return lean ? wide_kernel<8, 1, kWideWaves, 4, 2, true> : wide_kernel<8, 1, kWideWaves, 4, 2>;
     }
     return nullptr;
 }
@@ -454,12 +460,13 @@ WideKernel select_kernel(int mt16) {
 // Raises the dynamic LDS limit of every build on the current device (per-device set-up).
 fr_status prepare_wide_kernels() {
     for (const Build &b : kBuilds)
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(select_kernel(b.mt16)),
-                                hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kLdsBudget - kStaticLdsReserve) != hipSuccess) {
-            (void)hipGetLastError();
-            return FR_ERR_HIP;
-        }
+        for (int lean = 0; lean < 2; ++lean)
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(select_kernel(b.mt16, lean != 0)),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    kLdsBudget - kStaticLdsReserve) != hipSuccess) {
+                (void)hipGetLastError();
+                return FR_ERR_HIP;
+            }
     return FR_OK;
 }
 
@@ -514,7 +521,8 @@ fr_status launch_mfma(const HeadProblem &p, Sink sink, const fr_tuning *t, hipSt
     a.mailbox = sink == Sink::kFusedTopk && p.k <= kMailK && p.M <= kMailRows && grid <= 4 * kWave &&
                 !(t && t->no_mailbox);
 
-    const WideKernel kern = select_kernel(b->mt16);
+    const bool lean = sink == Sink::kFusedTopk && a.mailbox && !a.trace && a.spin_limit == 0u;
+    const WideKernel kern = select_kernel(b->mt16, lean);
     if (!kern) return FR_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kWideWaves * kWave), lds, s, a);
     const fr_status st = hip_status(hipGetLastError());
