@@ -116,8 +116,9 @@ struct SkinnyLds {
 // registers (212 against 220 vector registers, 162 against 217 scalar spills) and is worth 0.55 us per
 // call at every size.  (Fixing the wavefronts per tile along d, or M and k, at compile time as well
 // measured no further gain.)
+// LEAN = 2: the same with the fused beam-search step (fr_draft_step).
 template <int MT, int WAVES, int DEPTH, bool MFMA, bool TILED = false, bool SKEW = false, int HR = 16, bool B32 = false,
-          bool LEAN = false>
+          int LEAN = 0>
 __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     static_assert(MFMA || !TILED, "the tiled layout is the matrix cores' operand order");
     static_assert(!SKEW || (MFMA && !TILED), "the skewed build is the default build plus one wavefront");
@@ -202,15 +203,15 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
     }
     const bool has_tile = !SKEW || tile_in_pass * kTileRows < blk_rows;   // wave-uniform
     auto stamp = [&](int slot) {
-        if constexpr (!LEAN)
+        if constexpr (LEAN == 0)
             if (a.trace && tid == 0) a.trace[blockIdx.x * 8 + slot] = (long long)__builtin_amdgcn_s_memrealtime();
     };
-    const int sink = LEAN ? (int)Sink::kFusedTopk : a.sink;
+    const int sink = LEAN != 0 ? (int)Sink::kFusedTopk : a.sink;
     stamp(0);
     // which arrival counter this call uses: asked for now, needed at the very end
     const Arrival ar(a.ticket);
     // single launch, k <= 16, at most 256 workgroups: results travel as mailbox records
-    const bool mailbox = LEAN || (sink == (int)Sink::kFusedTopk && a.k <= kSmallKMax && G <= 4 * kWave);
+    const bool mailbox = LEAN != 0 || (sink == (int)Sink::kFusedTopk && a.k <= kSmallKMax && G <= 4 * kWave);
     const unsigned turn = (sink == (int)Sink::kFusedTopk && !mailbox) ? ar.turn() : 0u;
 
     // Step range of this wavefront along d, split into a pipelined part (whole groups of
@@ -541,8 +542,8 @@ __global__ __launch_bounds__(WAVES * kWave) void skinny_kernel(SkinnyArgs a) {
         const int r = (top - b) / spread;
         if (b > top || b % spread != 0 || r >= R) return;
         stamp(4);
-        const unsigned spin = LEAN ? kMailSpinLimit : (a.spin_limit ? a.spin_limit : kMailSpinLimit);
-        unsigned long long *const step_rec = LEAN ? nullptr : a.step.rec;
+        const unsigned spin = LEAN != 0 ? kMailSpinLimit : (a.spin_limit ? a.spin_limit : kMailSpinLimit);
+        unsigned long long *const step_rec = LEAN == 1 ? nullptr : a.step.rec;
         merge_rows_mailbox<(WAVES >= 8 ? 8 : 4), B32>(a.mail, part, a.ticket + 1, G, r, R, a.M, a.k, a.token_ids, a.logp, &s_merge,
                                                       &s_select[0], step_rec, spin);
         // the first merger also runs the beam-search expansion of the step, if one was asked for
@@ -624,23 +625,21 @@ constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 constexpr int kMfmaTile = 16;   // the matrix-core variant is compiled once, for up to 16 rows
 
 // The kernel build behind a variant, for M rows of H (MT: width of the vector-ALU tile).
-SkinnyKernel select_kernel(int variant, int M, int MT, bool b32 = false, bool lean = false) {
-    if (variant == 0 && lean) {   // the default build for the plain fused call: k <= 10, and k = 11 .. 16
-        if (b32) {
-            if (M <= 2) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 2, true, true>;
-            if (M <= 4) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 4, true, true>;
-            if (M <= 8) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 8, true, true>;
-            if (M <= 10) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 10, true, true>;
-            if (M <= 12) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 12, true, true>;
-            return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 16, true, true>;
-        }
-        if (M <= 2) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 2, false, true>;
-        if (M <= 4) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 4, false, true>;
-        if (M <= 8) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 8, false, true>;
-        if (M <= 10) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 10, false, true>;
-        if (M <= 12) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 12, false, true>;
-        return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 16, false, true>;
-    }
+template <bool B32, int LEAN>
+SkinnyKernel lean_kernel(int M) {
+    if (M <= 2) return skinny_kernel<16, 8, 4, true, false, false, 2, B32, LEAN>;
+    if (M <= 4) return skinny_kernel<16, 8, 4, true, false, false, 4, B32, LEAN>;
+    if (M <= 8) return skinny_kernel<16, 8, 4, true, false, false, 8, B32, LEAN>;
+    if (M <= 10) return skinny_kernel<16, 8, 4, true, false, false, 10, B32, LEAN>;
+    if (M <= 12) return skinny_kernel<16, 8, 4, true, false, false, 12, B32, LEAN>;
+    return skinny_kernel<16, 8, 4, true, false, false, 16, B32, LEAN>;
+}
+
+// lean: 0 = the general build, 1 = the build for the plain fused call, 2 = for the call with the fused
+// beam-search step (k <= 10 only)
+SkinnyKernel select_kernel(int variant, int M, int MT, bool b32 = false, int lean = 0) {
+    if (variant == 0 && lean == 1) return b32 ? lean_kernel<true, 1>(M) : lean_kernel<false, 1>(M);
+    if (variant == 0 && lean == 2 && !b32) return lean_kernel<false, 2>(M);
     if (variant == 0 && b32) {   // the default build for k = 11 .. 16
         if (M <= 2) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 2, true>;
         if (M <= 4) return skinny_kernel<kMfmaTile, 8, 4, true, false, false, 4, true>;
@@ -698,9 +697,9 @@ int default_variant(int M, int d, int k, bool vector_alu, bool tiled) {
 fr_status prepare_skinny_kernels() {
     for (int variant = 0; variant < kNumVariants; ++variant)
         for (int M = 1; M <= kSkinnyMaxM; ++M) {
-            for (int build = 0; build < 4; ++build) {   // 16 / 32 groups of the bound x general / lean
+            for (int build = 0; build < 6; ++build) {   // 16 / 32 groups of the bound x general / lean / lean with step
                 const SkinnyKernel kern = select_kernel(variant, M, kVariants[variant].mfma ? kMfmaTile : bucket_for(M),
-                                                        (build & 1) != 0, (build & 2) != 0);
+                                                        (build & 1) != 0, build >> 1);
                 if (!kern) return FR_ERR_HIP;
                 if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                         kLdsBudget - kStaticLdsReserve) != hipSuccess) {
@@ -823,9 +822,9 @@ fr_status launch_skinny(const HeadProblem &p, Sink sink, const fr_tuning *t, hip
     }
     const int lds = lds_bytes(p.M, p.d, p.k, variant);
 
-    const bool lean = sink == Sink::kFusedTopk && p.k <= kSmallKMax && grid <= 4 * kWave && !a.step.rec && !a.trace &&
-                      a.spin_limit == 0u;
-    const SkinnyKernel kern = select_kernel(variant, a.M, MT, p.k >= kBound32FromK && p.k <= kSmallKMax, lean);
+    const bool lean = sink == Sink::kFusedTopk && p.k <= kSmallKMax && grid <= 4 * kWave && !a.trace && a.spin_limit == 0u;
+    const SkinnyKernel kern = select_kernel(variant, a.M, MT, p.k >= kBound32FromK && p.k <= kSmallKMax,
+                                            !lean ? 0 : a.step.rec ? 2 : 1);
     if (!kern) return FR_ERR_INVALID_ARG;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kVariants[variant].waves * kWave), lds, s, a);
     const fr_status st = hip_status(hipGetLastError());
