@@ -234,6 +234,15 @@ def main() -> int:
     cfgs["sweep_V_sub_128256_full_topk"] = {"M": M, "d": d, "rows_of_W": V, "us_per_call_cold": t_full * 1e6,
                                             "calls_per_s": 1.0 / t_full, "algorithmic_gbps": V * d * 2 / t_full / 1e9,
                                             "hbm_frac": V * d * 2 / t_full / 1e9 / PEAK_HBM_GBPS}
+    # the headline shape at the edges of the fast path: one row of H (the first draft step), and k = 16
+    cfgs["headline_M1"] = leg(lambda i: fr.fr_draft_topk(H[:1], copies[i % N_COPIES], idx_map, k, ws, token_ids=ids[:1],
+                                                         logp=logp[:1]), 400, 20, V_sub, d, 1)
+    ids16 = torch.empty((M, 16), dtype=torch.int32, device="cuda")
+    lp16 = torch.empty((M, 16), dtype=torch.float32, device="cuda")
+    ws16 = fr.new_workspace(M, d, V, 16)
+    cfgs["headline_k16"] = leg(lambda i: fr.fr_draft_topk(H, copies[i % N_COPIES], idx_map, 16, ws16, token_ids=ids16,
+                                                          logp=lp16), 400, 20, V_sub, d, M)
+    cfgs["headline_k16"]["k"] = 16
     gen_dev = torch.Generator(device="cuda")
     gen_dev.manual_seed(20250214)
     # batched drafting: M = 256 rows of H against the same subset; the full head at M = 64
