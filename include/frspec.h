@@ -139,8 +139,11 @@ fr_status fr_workspace_check(const void *workspace, size_t workspace_bytes, int3
  * rounded up to a multiple of 16) must not exceed 4 GiB, else FR_ERR_UNSUPPORTED.
  * M <= 16 runs in the skinny kernel (all of H resident in LDS, W streamed once through
  * registers) while H fits beside the kernel's other LDS buffers (12 rows at d = 4096);
- * larger M, or a larger H, runs in the chunked matrix-core kernel in slabs of up to 128
- * rows of H (one pass over W_sub per slab).
+ * larger M, or a larger H, runs in the matrix-core kernels: up to 64 rows of H in the chunked
+ * kernel, 65 to 256 rows per launch in the block kernel (one pass over W_sub for all of them;
+ * d a multiple of 128, k <= 16), otherwise in slabs of up to 128 rows of H, one pass per slab.
+ * k <= 16 takes the fast selection and the single-launch merge at every M (k = 11 .. 16 within
+ * about 1.5 us of k = 10); larger k takes a general path that costs two to five times as much.
  * NaN or infinite inputs give unspecified outputs but never a fault or a hang.
  */
 fr_status fr_draft_topk(const void *H, int64_t M, int64_t d,
