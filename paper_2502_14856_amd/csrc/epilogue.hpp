@@ -967,23 +967,45 @@ __device__ __forceinline__ void expand_step_fused(const StepArgs &st, int M, int
             st.hist_score[st.hist_offset + c] = score[q];
             st.hist_token[st.hist_offset + c] = (int)(unsigned)r[q];
             st.hist_parent[st.hist_offset + c] = st.node_hist[row[q]];
-            keys[c] = make_key(key_hi_of(score[q]), ~(unsigned)c);
         }
     }
-    if (lane == 0) keys[C] = 0ull;
+    // Only the `width` best are wanted, not every candidate's rank: the candidates fall into 16 groups
+    // (lanes l, l + 16, l + 32, l + 48, all their candidates); the width-th largest group maximum is a
+    // lower bound of the width-th best score; the candidates at or above it (width plus a few) are
+    // packed into `keys` and ranked among themselves.
+    unsigned khi[CPL];
+    unsigned lm = 0u;
+#pragma unroll
+    for (int q = 0; q < CPL; ++q) {
+        khi[q] = inb[q] ? key_hi_of(score[q]) : 0u;
+        lm = max(lm, khi[q]);
+    }
+    const unsigned gm = max_xor32_u32(max_xor16_u32(lm));
+    const unsigned bound = st.width <= 16 ? row16_kth_largest_u32(gm, st.width) : 0u;
+    int n = 0;
+    bool sv[CPL];
+#pragma unroll
+    for (int q = 0; q < CPL; ++q) {
+        sv[q] = khi[q] != 0u && khi[q] >= bound;
+        const unsigned long long mask = __ballot(sv[q]);
+        const int pos = n + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0u));
+        if (sv[q]) keys[pos] = make_key(khi[q], ~(unsigned)(lane + kWave * q));
+        n += (int)__popcll(mask);
+    }
+    if (lane == 0) keys[n] = 0ull;
     // (one wavefront: its LDS operations execute in order, no barrier needed)
     const u64x2 *kp = reinterpret_cast<const u64x2 *>(keys);
 #pragma unroll
     for (int q = 0; q < CPL; ++q) {
-        if (__ballot(inb[q]) == 0ull) continue;
-        const unsigned long long mine = inb[q] ? keys[lane + kWave * q] : ~0ull;
+        if (__ballot(sv[q]) == 0ull) continue;
+        const unsigned long long mine = sv[q] ? make_key(khi[q], ~(unsigned)(lane + kWave * q)) : ~0ull;
         int rank = 0;
-        for (int j = 0; j < C; j += 2) {
+        for (int j = 0; j < n; j += 2) {
             const u64x2 two = kp[j >> 1];
             rank += two.x > mine;
             rank += two.y > mine;
         }
-        if (inb[q] && rank < st.width) {
+        if (sv[q] && rank < st.width) {
             st.next_score[rank] = score[q];
             st.next_token[rank] = (int)(unsigned)r[q];
             st.next_hist[rank] = (int)(st.hist_offset + lane + kWave * q);
