@@ -420,7 +420,7 @@ def main() -> int:
                      "traffic_source": TRAFFIC_PROFILE + " (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE per launch of "
                                        "this kernel, scaled by a plain read of known size; a committed summary, "
                                        "not measured in this run)",
-                     "kernel": "skinny_kernel<16,8,4,true,false,false,10,false,true> (matrix-core build for k <= 10, lean, one launch per call: stream, fold, mailbox merge)",
+                     "kernel": "skinny_kernel<16,8,4,true,false,false,10,false,1> (matrix-core build for k <= 10, lean, one launch per call: stream, fold, mailbox merge)",
                      "algorithmic_bytes_per_launch": bytes_per_call},
         "cpu_baseline": cpu,
         "extra": {
